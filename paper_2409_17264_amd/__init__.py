@@ -1,0 +1,16 @@
+"""MI355X-native paged attention for chunked prefill, split-KV decode and the
+log-sum-exp merge of KV-cache parallelism (hand-written HIP behind a C ABI).
+
+The Python layer only marshals arguments; every step runs in the HIP library.
+The library is loaded on first use and a missing library is an error.
+"""
+from .binding import (  # noqa: F401
+    MedhaError,
+    chunked_prefill_attn,
+    chunked_prefill_workspace_bytes,
+    decode_partial_attn,
+    decode_partial_workspace_bytes,
+    library_path,
+    load_library,
+    lse_merge,
+)
