@@ -1,0 +1,263 @@
+// C ABI of the gfx950 paged-attention library: argument validation, launch
+// planning and kernel launches.  See include/medha.h for the contract.
+#include "medha.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "attn_kernel.h"
+#include "common.h"
+#include "merge_kernel.h"
+#include "planner.h"
+
+namespace medha {
+namespace {
+
+int current_num_cus() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      cus <= 0) {
+    (void)hipGetLastError();
+    return 256;  // MI355X; used only for planning queries made without a device
+  }
+  return cus;
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int check_heads(int h_q, int h_kv, int d, int page_size) {
+  if (h_q <= 0 || h_kv <= 0 || h_q % h_kv != 0) return MEDHA_ERR_INVALID_ARG;
+  if (page_size != kPageSize || (d != 64 && d != 128)) return MEDHA_ERR_UNSUPPORTED;
+  return MEDHA_OK;
+}
+
+template <int D, int QB, bool SPLIT_KEYS>
+hipError_t launch_attn(const AttnArgs& a, int grid, hipStream_t stream) {
+  hipLaunchKernelGGL((attn_kernel<D, QB, SPLIT_KEYS>), dim3(grid), dim3(kThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_plan(const LaunchPlan& lp, bool split_keys, int d, AttnArgs& a,
+                       void* descs_dev, hipStream_t stream) {
+  if (lp.descs.empty() || lp.n_slots == 0) return hipSuccess;
+  a.n_seq = (int)lp.descs.size();
+  a.descs = nullptr;
+  if (a.n_seq <= kMaxInlineSeq) {
+    std::memcpy(a.inline_descs, lp.descs.data(), lp.descs.size() * sizeof(SeqDesc));
+  } else {
+    // Pageable source: the runtime has consumed the host buffer when this returns.
+    hipError_t e = hipMemcpyAsync(descs_dev, lp.descs.data(), lp.descs.size() * sizeof(SeqDesc),
+                                  hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) return e;
+    a.descs = static_cast<const SeqDesc*>(descs_dev);
+  }
+  hipError_t e;
+  if (split_keys) {
+    e = d == 128 ? launch_attn<128, 1, true>(a, lp.n_slots, stream)
+                 : launch_attn<64, 1, true>(a, lp.n_slots, stream);
+  } else if (lp.q_blocks == 2) {
+    e = d == 128 ? launch_attn<128, 2, false>(a, lp.n_slots, stream)
+                 : launch_attn<64, 2, false>(a, lp.n_slots, stream);
+  } else {
+    e = d == 128 ? launch_attn<128, 1, false>(a, lp.n_slots, stream)
+                 : launch_attn<64, 1, false>(a, lp.n_slots, stream);
+  }
+  if (e != hipSuccess || !lp.any_split) return e;
+
+  MergeArgs m{};
+  m.part_o = a.part_o;
+  m.part_lse = a.part_lse;
+  m.out = a.out;
+  m.lse = a.lse;
+  m.descs = a.descs;
+  m.n_seq = a.n_seq;
+  m.h_q = a.h_q;
+  m.total_rows = lp.total_rows;
+  if (a.n_seq <= kMaxInlineSeq)
+    std::memcpy(m.inline_descs, lp.descs.data(), lp.descs.size() * sizeof(SeqDesc));
+  const int64_t threads = (int64_t)lp.total_rows * a.h_q * (d / 4);
+  const int grid = (int)ceil_div(threads, kThreads);
+  if (d == 128)
+    hipLaunchKernelGGL(split_merge_kernel<128>, dim3(grid), dim3(kThreads), 0, stream, m);
+  else
+    hipLaunchKernelGGL(split_merge_kernel<64>, dim3(grid), dim3(kThreads), 0, stream, m);
+  return hipGetLastError();
+}
+
+int run_plan(const Plan& plan, const void* q, const medha_kv_cache* kv, const int32_t* page_table,
+             int h_q, float softmax_scale, float* out, float* lse, void* workspace,
+             size_t workspace_bytes, void* hip_stream) {
+  if (plan.bytes > 256 || plan.part_rows > 0) {
+    if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < plan.bytes)
+      return MEDHA_ERR_WORKSPACE;
+  }
+  char* ws = static_cast<char*>(workspace);
+  AttnArgs a{};
+  a.q = static_cast<const __bf16*>(q);
+  a.k_pool = static_cast<const __bf16*>(kv->k_pool);
+  a.v_pool = static_cast<const __bf16*>(kv->v_pool);
+  a.page_table = page_table;
+  a.out = out;
+  a.lse = lse;
+  a.part_o = ws ? reinterpret_cast<float*>(ws + plan.off_part_o) : nullptr;
+  a.part_lse = ws ? reinterpret_cast<float*>(ws + plan.off_part_lse) : nullptr;
+  a.h_q = h_q;
+  a.h_kv = kv->num_kv_heads;
+  a.scale_log2 = softmax_scale * kLog2e;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (launch_plan(plan.rows, false, kv->head_dim, a, ws ? ws + plan.off_descs_rows : nullptr,
+                  stream) != hipSuccess)
+    return MEDHA_ERR_HIP;
+  if (launch_plan(plan.keys, true, kv->head_dim, a, ws ? ws + plan.off_descs_keys : nullptr,
+                  stream) != hipSuccess)
+    return MEDHA_ERR_HIP;
+  return MEDHA_OK;
+}
+
+int check_kv(const medha_kv_cache* kv, int h_q) {
+  if (kv == nullptr || kv->k_pool == nullptr || kv->v_pool == nullptr || kv->num_pages <= 0)
+    return MEDHA_ERR_INVALID_ARG;
+  if (!aligned(kv->k_pool, 16) || !aligned(kv->v_pool, 16)) return MEDHA_ERR_INVALID_ARG;
+  return check_heads(h_q, kv->num_kv_heads, kv->head_dim, kv->page_size);
+}
+
+}  // namespace
+}  // namespace medha
+
+using namespace medha;
+
+extern "C" {
+
+int medha_abi_version(void) { return 1; }
+
+const char* medha_strerror(int code) {
+  switch (code) {
+    case MEDHA_OK: return "ok";
+    case MEDHA_ERR_INVALID_ARG: return "invalid argument";
+    case MEDHA_ERR_UNSUPPORTED: return "unsupported shape (page size 16, head_dim 64 or 128, GQA group <= 32 for decode)";
+    case MEDHA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case MEDHA_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error code";
+  }
+}
+
+size_t medha_chunked_prefill_workspace_bytes(const int32_t* prefix_len, const int32_t* chunk_len,
+                                             int32_t batch, int32_t num_q_heads,
+                                             int32_t num_kv_heads, int32_t head_dim) {
+  if (batch < 0 || (batch > 0 && (prefix_len == nullptr || chunk_len == nullptr))) return 0;
+  if (check_heads(num_q_heads, num_kv_heads, head_dim, kPageSize) != MEDHA_OK) return 0;
+  std::vector<SeqInput> seqs(batch);
+  int64_t row = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (prefix_len[b] < 0 || chunk_len[b] < 1) return 0;
+    if ((int64_t)prefix_len[b] + chunk_len[b] > INT32_MAX) return 0;
+    seqs[b] = SeqInput{0, (int32_t)row, (int32_t)row, chunk_len[b], prefix_len[b]};
+    row += chunk_len[b];
+    if (row > INT32_MAX) return 0;
+  }
+  return make_plan(seqs.data(), batch, num_q_heads, num_kv_heads, head_dim, current_num_cus())
+      .bytes;
+}
+
+int medha_chunked_prefill_attn(const void* q, const medha_kv_cache* kv, const int32_t* page_table,
+                               const int64_t* page_table_offs, const int32_t* prefix_len,
+                               const int32_t* chunk_len, int32_t batch, int32_t num_q_heads,
+                               float softmax_scale, float* out, float* lse, void* workspace,
+                               size_t workspace_bytes, void* hip_stream) {
+  if (batch < 0) return MEDHA_ERR_INVALID_ARG;
+  int rc = check_kv(kv, num_q_heads);
+  if (rc != MEDHA_OK) return rc;
+  if (batch == 0) return MEDHA_OK;
+  if (q == nullptr || page_table == nullptr || page_table_offs == nullptr ||
+      prefix_len == nullptr || chunk_len == nullptr || out == nullptr || lse == nullptr)
+    return MEDHA_ERR_INVALID_ARG;
+  if (!aligned(q, 16) || !aligned(out, 16) || !aligned(lse, 4) || !std::isfinite(softmax_scale))
+    return MEDHA_ERR_INVALID_ARG;
+  std::vector<SeqInput> seqs(batch);
+  int64_t row = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (prefix_len[b] < 0 || chunk_len[b] < 1) return MEDHA_ERR_INVALID_ARG;
+    const int64_t n = (int64_t)prefix_len[b] + chunk_len[b];
+    if (n > INT32_MAX) return MEDHA_ERR_INVALID_ARG;
+    const int64_t have = page_table_offs[b + 1] - page_table_offs[b];
+    if (page_table_offs[b] < 0 || have < ceil_div(n, kPageSize)) return MEDHA_ERR_INVALID_ARG;
+    seqs[b] = SeqInput{page_table_offs[b], (int32_t)row, (int32_t)row, chunk_len[b], prefix_len[b]};
+    row += chunk_len[b];
+    if (row > INT32_MAX) return MEDHA_ERR_INVALID_ARG;
+  }
+  const Plan plan = make_plan(seqs.data(), batch, num_q_heads, kv->num_kv_heads, kv->head_dim,
+                              current_num_cus());
+  return run_plan(plan, q, kv, page_table, num_q_heads, softmax_scale, out, lse, workspace,
+                  workspace_bytes, hip_stream);
+}
+
+size_t medha_decode_partial_workspace_bytes(const int32_t* kv_len, int32_t items,
+                                            int32_t num_q_heads, int32_t num_kv_heads,
+                                            int32_t head_dim) {
+  if (items < 0 || (items > 0 && kv_len == nullptr)) return 0;
+  if (check_heads(num_q_heads, num_kv_heads, head_dim, kPageSize) != MEDHA_OK) return 0;
+  if (num_q_heads / num_kv_heads > 32) return 0;
+  std::vector<SeqInput> seqs(items);
+  for (int i = 0; i < items; ++i) {
+    if (kv_len[i] < 0) return 0;
+    seqs[i] = SeqInput{0, 0, i, 1, kv_len[i] - 1};
+  }
+  return make_plan(seqs.data(), items, num_q_heads, num_kv_heads, head_dim, current_num_cus())
+      .bytes;
+}
+
+int medha_decode_partial_attn(const void* q, int32_t num_queries, const medha_kv_cache* kv,
+                              const int32_t* page_table, const int64_t* page_table_offs,
+                              const int32_t* q_index, const int32_t* kv_len, int32_t items,
+                              int32_t num_q_heads, float softmax_scale, float* out_partial,
+                              float* lse_partial, void* workspace, size_t workspace_bytes,
+                              void* hip_stream) {
+  if (items < 0 || num_queries < 0) return MEDHA_ERR_INVALID_ARG;
+  int rc = check_kv(kv, num_q_heads);
+  if (rc != MEDHA_OK) return rc;
+  if (num_q_heads / kv->num_kv_heads > 32) return MEDHA_ERR_UNSUPPORTED;
+  if (items == 0) return MEDHA_OK;
+  if (q == nullptr || page_table == nullptr || page_table_offs == nullptr || q_index == nullptr ||
+      kv_len == nullptr || out_partial == nullptr || lse_partial == nullptr)
+    return MEDHA_ERR_INVALID_ARG;
+  if (!aligned(q, 16) || !aligned(out_partial, 16) || !aligned(lse_partial, 4) ||
+      !std::isfinite(softmax_scale))
+    return MEDHA_ERR_INVALID_ARG;
+  std::vector<SeqInput> seqs(items);
+  for (int i = 0; i < items; ++i) {
+    if (kv_len[i] < 0 || q_index[i] < 0 || q_index[i] >= num_queries) return MEDHA_ERR_INVALID_ARG;
+    const int64_t have = page_table_offs[i + 1] - page_table_offs[i];
+    if (page_table_offs[i] < 0 || have < ceil_div(kv_len[i], kPageSize))
+      return MEDHA_ERR_INVALID_ARG;
+    seqs[i] = SeqInput{page_table_offs[i], q_index[i], i, 1, kv_len[i] - 1};
+  }
+  const Plan plan = make_plan(seqs.data(), items, num_q_heads, kv->num_kv_heads, kv->head_dim,
+                              current_num_cus());
+  return run_plan(plan, q, kv, page_table, num_q_heads, softmax_scale, out_partial, lse_partial,
+                  workspace, workspace_bytes, hip_stream);
+}
+
+int medha_lse_merge(const float* out_partial, const float* lse_partial, int32_t num_splits,
+                    int64_t rows, int32_t num_q_heads, int32_t head_dim, float* out, float* lse,
+                    void* hip_stream) {
+  if (num_splits < 1 || rows < 0 || num_q_heads <= 0 || head_dim <= 0)
+    return MEDHA_ERR_INVALID_ARG;
+  if (head_dim % 4 != 0) return MEDHA_ERR_UNSUPPORTED;
+  if (rows == 0) return MEDHA_OK;
+  if (out_partial == nullptr || lse_partial == nullptr || out == nullptr || lse == nullptr)
+    return MEDHA_ERR_INVALID_ARG;
+  if (!aligned(out_partial, 16) || !aligned(out, 16)) return MEDHA_ERR_INVALID_ARG;
+  const int64_t threads = rows * num_q_heads * (head_dim / 4);
+  const int64_t grid = ceil_div(threads, kThreads);
+  if (grid > INT32_MAX) return MEDHA_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(lse_merge_kernel, dim3((unsigned)grid), dim3(kThreads), 0,
+                     static_cast<hipStream_t>(hip_stream), out_partial, lse_partial, num_splits,
+                     rows, num_q_heads, head_dim, out, lse);
+  return hipGetLastError() == hipSuccess ? MEDHA_OK : MEDHA_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,50 @@
+"""Glue for the GPU parity tests: run a workload through the C ABI (via the
+binding) and through the CPU oracle on the same bits."""
+import numpy as np
+import torch
+
+import oracle
+import paper_2409_17264_amd as medha
+from paper_2409_17264_amd import workloads as wl
+
+O_TOL = 1e-2      # max-abs tolerance on O   (bf16 inputs, fp32 accumulation)
+LSE_TOL = 1e-3    # max-abs tolerance on LSE
+
+
+def to_dev(batch):
+    dev = torch.device("cuda:0")
+    batch.q = batch.q.to(dev)
+    batch.k_pool = batch.k_pool.to(dev)
+    batch.v_pool = batch.v_pool.to(dev)
+    return batch
+
+
+def gpu_prefill(batch):
+    pt = torch.from_numpy(batch.page_table).to("cuda:0")
+    out, lse = medha.chunked_prefill_attn(batch.q, batch.k_pool, batch.v_pool, pt,
+                                          batch.page_table_offs, batch.prefix_len,
+                                          batch.chunk_len, batch.scale)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), lse.cpu().numpy()
+
+
+def oracle_prefill(batch, rows=None):
+    return oracle.chunked_prefill_attn(wl.bf16_bits(batch.q), wl.bf16_bits(batch.k_pool),
+                                       wl.bf16_bits(batch.v_pool), batch.page_table,
+                                       batch.page_table_offs, batch.prefix_len, batch.chunk_len,
+                                       batch.scale, rows)
+
+
+def check(out, lse, ref_out, ref_lse, what=""):
+    assert np.isfinite(out).all(), f"{what}: non-finite O"
+    fin = np.isfinite(ref_lse)
+    assert np.array_equal(np.isneginf(lse), np.isneginf(ref_lse)), f"{what}: -inf pattern"
+    eo = float(np.max(np.abs(out - ref_out))) if out.size else 0.0
+    el = float(np.max(np.abs(lse[fin] - ref_lse[fin]))) if fin.any() else 0.0
+    scale = float(np.max(np.abs(ref_out))) if out.size else 1.0
+    print(f"[parity] {what}: max|dO|={eo:.3e} (max|O|={scale:.3e}) max|dLSE|={el:.3e}", flush=True)
+    assert eo <= O_TOL, f"{what}: O error {eo}"
+    assert el <= LSE_TOL, f"{what}: LSE error {el}"
+    # tighter, relative: bf16 rounding of the probabilities is the only large error source
+    assert eo <= 2e-2 * max(scale, 1e-6) + 1e-6, f"{what}: relative O error {eo / scale}"
+    return eo, el

@@ -1,0 +1,79 @@
+"""GPU parity on the named workloads: scaled-down versions against the full
+oracle, and the published sizes against oracle rows sampled one by one."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2409_17264_amd as medha
+from paper_2409_17264_amd import workloads as wl
+from tests.gpu_util import check, gpu_prefill, oracle_prefill, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config2_scaled_full_oracle():
+    b = to_dev(wl.config2_llama8b("cpu", prefix=2048, chunk=384))
+    out, lse = gpu_prefill(b)
+    ro, rl = oracle_prefill(b)
+    check(out, lse, ro, rl, "cfg2 scaled (P2048 c384)")
+
+
+def test_config4_scaled_split_kv_full_oracle():
+    """8 q heads / 1 kv head with a long prefix and a small chunk: few row tiles,
+    so the KV axis is split across workgroups and merged."""
+    b = to_dev(wl.config4_llama70b_tp(128, "cpu", prefix=40000, max_chunk=128))
+    out, lse = gpu_prefill(b)
+    ro, rl = oracle_prefill(b)
+    check(out, lse, ro, rl, "cfg4 scaled (P40000 c128)")
+
+
+def test_config5_scaled_mixed_batch_full_oracle():
+    b = to_dev(wl.config5_mixed("cpu", prefix=8192, chunk=256, n_decode=64))
+    out, lse = gpu_prefill(b)
+    rows = np.concatenate([wl.sample_rows(256, 5, 8, 8, 32), np.arange(256, 256 + 64)])
+    ro, rl = oracle_prefill(b, rows)
+    check(out[rows], lse[rows], ro, rl, "cfg5 scaled (P8192 c256 + 64 decodes)")
+
+
+def test_config2_full_size_sampled_rows():
+    b = wl.config2_llama8b("cuda:0")
+    out, lse = gpu_prefill(b)
+    rows = wl.sample_rows(b.tokens, 2, 4, 4, 8)
+    ro, rl = oracle_prefill(b, rows)
+    check(out[rows], lse[rows], ro, rl, "cfg2 full size, 16 sampled rows x 32 heads")
+
+
+def test_config4_full_size_sampled_rows():
+    for chunk in (512, 2048):
+        b = wl.config4_llama70b_tp(chunk, "cuda:0")
+        out, lse = gpu_prefill(b)
+        rows = np.array([0, chunk // 2 + 1, chunk - 1], np.int64)
+        ro, rl = oracle_prefill(b, rows)
+        check(out[rows], lse[rows], ro, rl, f"cfg4 c{chunk} full size, 3 sampled rows x 8 heads")
+        del b
+        torch.cuda.empty_cache()
+
+
+def test_config3_full_size_kvp_decode():
+    """1M-token context, 4 shards of 262,144, merged; the oracle computes the
+    unsplit attention of all 32 heads."""
+    c = wl.config3_kvp_decode("cuda:0")
+    pt = torch.from_numpy(c.page_table).cuda()
+    po, pl = medha.decode_partial_attn(c.q, c.k_pool, c.v_pool, pt, c.shard_offs, c.q_index,
+                                       c.shard_len, c.scale)
+    o, l = medha.lse_merge(po[:, None].contiguous(), pl[:, None].contiguous())
+    torch.cuda.synchronize()
+    ro, rl = oracle.decode_partial_attn(wl.bf16_bits(c.q), wl.bf16_bits(c.k_pool),
+                                        wl.bf16_bits(c.v_pool), c.page_table,
+                                        np.array([0, len(c.page_table)], np.int64), [0],
+                                        [c.context], c.scale)
+    check(o.cpu().numpy(), l.cpu().numpy(), ro, rl, "cfg3 full size merged vs unsplit oracle")
+
+
+def test_config5_full_size_sampled_rows():
+    b = wl.config5_mixed("cuda:0")
+    out, lse = gpu_prefill(b)
+    rows = np.concatenate([np.array([0, 511, 1023]), np.arange(1024, 1024 + 64)]).astype(np.int64)
+    ro, rl = oracle_prefill(b, rows)
+    check(out[rows], lse[rows], ro, rl, "cfg5 full size: 3 prefill rows + all 64 decodes")

@@ -1,0 +1,223 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+element by element on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2409_17264_amd as medha
+from paper_2409_17264_amd import workloads as wl
+from tests.gpu_util import (LSE_TOL, O_TOL, check, gpu_prefill, oracle_prefill, to_dev)
+
+pytestmark = pytest.mark.gpu
+
+
+# ----------------------------------------------------------------- lse merge
+@pytest.mark.parametrize("splits,rows,h_q,d", [(1, 3, 2, 64), (4, 1, 32, 128), (7, 33, 5, 128),
+                                               (2, 1000, 8, 64), (16, 17, 3, 32)])
+def test_lse_merge_matches_oracle(splits, rows, h_q, d):
+    rng = np.random.default_rng(splits * 1000 + rows)
+    po = rng.standard_normal((splits, rows, h_q, d)).astype(np.float32)
+    pl = (rng.standard_normal((splits, rows, h_q)) * 4).astype(np.float32)
+    if splits > 1:
+        pl[0, 0, :] = -np.inf              # an empty shard
+        pl[:, rows - 1, 0] = -np.inf       # a row with no keys at all
+    ro, rl = oracle.lse_merge(po.astype(np.float64), pl.astype(np.float64))
+    o, l = medha.lse_merge(torch.from_numpy(po).cuda(), torch.from_numpy(pl).cuda())
+    torch.cuda.synchronize()
+    o, l = o.cpu().numpy(), l.cpu().numpy()
+    assert np.array_equal(np.isneginf(l), np.isneginf(rl))
+    fin = np.isfinite(rl)
+    assert np.max(np.abs(o - ro)) < 1e-5
+    assert np.max(np.abs(l[fin] - rl[fin])) < 1e-5
+
+
+# ------------------------------------------------------------ config 1, tiny
+def test_config1_tiny_full_parity():
+    b = to_dev(wl.config1_tiny("cpu"))
+    out, lse = gpu_prefill(b)
+    ro, rl = oracle_prefill(b)
+    check(out, lse, ro, rl, "cfg1")
+
+
+# ------------------------------------------------- adversarial small shapes
+SHAPES = [(2, 1, 64), (8, 2, 128), (4, 4, 64), (8, 1, 128), (32, 8, 128)]
+CASES = [(0, 1), (0, 17), (1, 2), (15, 16), (16, 33), (63, 1), (64, 64), (65, 100), (200, 300),
+         (1000, 70), (37, 513)]
+
+
+@pytest.mark.parametrize("h_q,h_kv,d", SHAPES)
+@pytest.mark.parametrize("prefix,chunk", CASES)
+def test_small_shapes(h_q, h_kv, d, prefix, chunk):
+    if h_q == 32 and chunk > 100:
+        pytest.skip("covered by the scaled configs")
+    b = to_dev(wl.make_prefill_batch("s", h_q, h_kv, d, [prefix], [chunk],
+                                     seed=prefix * 7 + chunk, poison_unused=True))
+    out, lse = gpu_prefill(b)
+    ro, rl = oracle_prefill(b)
+    check(out, lse, ro, rl, f"hq{h_q} hkv{h_kv} d{d} P{prefix} c{chunk}")
+
+
+def test_ragged_batch_mixed_modes():
+    """Prefill chunks of several sizes and decodes (chunk_len 1) in one call,
+    with NaN in every unused pool slot and extra unreferenced pages."""
+    prefix = [300, 0, 77, 1500, 15, 16, 4000, 0]
+    chunk = [130, 40, 1, 1, 1, 2, 260, 1]
+    b = to_dev(wl.make_prefill_batch("rag", 8, 2, 128, prefix, chunk, seed=123,
+                                     num_pages=600, poison_unused=True))
+    out, lse = gpu_prefill(b)
+    ro, rl = oracle_prefill(b)
+    check(out, lse, ro, rl, "ragged batch")
+
+
+# ------------------------------------------------------------------ decode
+@pytest.mark.parametrize("h_q,h_kv,d", [(32, 8, 128), (8, 1, 128), (2, 1, 64), (4, 4, 64)])
+def test_decode_partial_lengths(h_q, h_kv, d):
+    lens = np.array([0, 1, 15, 16, 17, 127, 128, 129, 511, 1000, 5000, 20000], np.int32)
+    items = len(lens)
+    need = [wl.pages_for(int(n)) for n in lens]
+    num_pages = sum(need) + 5
+    pt, offs = wl.permuted_page_tables(need, num_pages, 77)
+    q = wl.randn_bf16((3, h_q, d), 1, "cpu")
+    k = wl.randn_bf16((num_pages, h_kv, 16, d), 2, "cpu")
+    v = wl.randn_bf16((num_pages, h_kv, 16, d), 3, "cpu")
+    wl.poison_unused_slots(k, v, pt, offs, lens)
+    q_index = (np.arange(items) % 3).astype(np.int32)
+    scale = d ** -0.5
+    ro, rl = oracle.decode_partial_attn(wl.bf16_bits(q), wl.bf16_bits(k), wl.bf16_bits(v), pt,
+                                        offs, q_index, lens, scale)
+    o, l = medha.decode_partial_attn(q.cuda(), k.cuda(), v.cuda(), torch.from_numpy(pt).cuda(),
+                                     offs, q_index, lens, scale)
+    torch.cuda.synchronize()
+    check(o.cpu().numpy(), l.cpu().numpy(), ro, rl, f"decode hq{h_q} hkv{h_kv} d{d}")
+
+
+def test_kvp_shards_merge_equals_unsplit_scaled_config3():
+    """Config 3 at 1/16 scale: 65,536-token context in 4 shards, merged, against
+    the oracle's unsplit attention (full oracle)."""
+    c = wl.config3_kvp_decode("cpu", context=65536)
+    ro, rl = oracle.decode_partial_attn(wl.bf16_bits(c.q), wl.bf16_bits(c.k_pool),
+                                        wl.bf16_bits(c.v_pool), c.page_table,
+                                        np.array([0, len(c.page_table)], np.int64), [0],
+                                        [c.context], c.scale)
+    pto = c.shard_offs
+    po, pl = medha.decode_partial_attn(c.q.cuda(), c.k_pool.cuda(), c.v_pool.cuda(),
+                                       torch.from_numpy(c.page_table).cuda(), pto, c.q_index,
+                                       c.shard_len, c.scale)
+    # per-shard partials against the oracle's partials
+    so, sl = oracle.decode_partial_attn(wl.bf16_bits(c.q), wl.bf16_bits(c.k_pool),
+                                        wl.bf16_bits(c.v_pool), c.page_table, pto, c.q_index,
+                                        c.shard_len, c.scale)
+    torch.cuda.synchronize()
+    check(po.cpu().numpy(), pl.cpu().numpy(), so, sl, "cfg3/16 shard partials")
+    o, l = medha.lse_merge(po[:, None].contiguous(), pl[:, None].contiguous())
+    torch.cuda.synchronize()
+    check(o.cpu().numpy(), l.cpu().numpy(), ro, rl, "cfg3/16 merged vs unsplit")
+
+
+# -------------------------------------------- bit-exact indexing through attention
+def test_needle_is_bit_exact_on_gpu():
+    """A key scoring far above all others takes the whole softmax mass in fp32
+    too, so O must equal that key's V row bit for bit: an end-to-end check of the
+    page-table gather through the attention kernels (row-split and key-split)."""
+    h_q, h_kv, d, P = 8, 2, 128, 700
+    for chunk in (1, 70):
+        for needle in (0, 15, 16, 63, 64, 127, 128, 511, 699, P + chunk - 1, P + 5):
+            if needle >= P + chunk:
+                continue
+            b = wl.make_prefill_batch("n", h_q, h_kv, d, [P], [chunk], seed=needle + chunk,
+                                      poison_unused=True)
+            b.q.fill_(1.0)
+            valid = ~torch.isnan(b.k_pool.float())
+            b.k_pool[valid] = 0
+            page, slot = int(b.page_table[needle // 16]), needle % 16
+            b.k_pool[page, :, slot, :] = 64.0
+            b = to_dev(b)
+            out, lse = gpu_prefill(b)
+            v = b.v_pool.float().cpu().numpy()
+            s_needle = np.float32(b.scale) * np.float32(d * 64.0)
+            for j in range(chunk):
+                for h in range(h_q):
+                    if needle <= P + j:
+                        assert np.array_equal(out[j, h], v[page, h // (h_q // h_kv), slot]), \
+                            (chunk, needle, j, h)
+                        assert abs(lse[j, h] - s_needle) < 1e-3
+                    else:
+                        assert abs(lse[j, h] - np.log(P + j + 1)) < 1e-3
+
+
+def test_page_permutation_is_bitwise_invariant_on_gpu():
+    a = wl.make_prefill_batch("a", 8, 2, 128, [1000, 300], [200, 1], seed=5)
+    num_pages = a.num_pages + 11
+    rng = np.random.default_rng(3)
+    perm = rng.permutation(num_pages).astype(np.int32)[:len(a.page_table)]
+    k2 = torch.zeros(num_pages, 2, 16, 128, dtype=torch.bfloat16)
+    v2 = torch.zeros_like(k2)
+    k2[perm.astype(np.int64)] = a.k_pool[a.page_table.astype(np.int64)]
+    v2[perm.astype(np.int64)] = a.v_pool[a.page_table.astype(np.int64)]
+    wl.poison_unused_slots(k2, v2, perm, a.page_table_offs, a.prefix_len + a.chunk_len)
+    a = to_dev(a)
+    o1, l1 = gpu_prefill(a)
+    o1b, l1b = gpu_prefill(a)
+    assert np.array_equal(o1, o1b) and np.array_equal(l1, l1b)      # run-to-run determinism
+    a.k_pool, a.v_pool, a.page_table = k2.cuda(), v2.cuda(), perm
+    o2, l2 = gpu_prefill(a)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+def test_chunk_by_chunk_equals_one_shot_on_gpu():
+    """Processing a sequence in ragged chunks gives the same rows as one causal
+    pass (within tolerance; the tile schedule differs)."""
+    n = 900
+    full = to_dev(wl.make_prefill_batch("f", 8, 2, 128, [0], [n], seed=17))
+    fo, fl = gpu_prefill(full)
+    ro, rl = oracle_prefill(full)
+    check(fo, fl, ro, rl, "one-shot causal")
+    start = 0
+    for c in (1, 100, 33, 256, 510):
+        part = wl.PrefillBatch("p", 8, 2, 128, np.array([start], np.int32),
+                               np.array([c], np.int32), full.page_table, full.page_table_offs,
+                               full.num_pages, full.q[start:start + c].contiguous(), full.k_pool,
+                               full.v_pool, full.scale)
+        o, l = gpu_prefill(part)
+        check(o, l, ro[start:start + c], rl[start:start + c], f"chunk@{start}+{c}")
+        start += c
+    assert start == n
+
+
+# ---------------------------------------------------------- error handling
+def test_invalid_arguments_are_rejected_without_writing():
+    b = to_dev(wl.make_prefill_batch("e", 8, 2, 128, [100], [10], seed=1))
+    pt = torch.from_numpy(b.page_table).cuda()
+    out = torch.full((10, 8, 128), 7.0, device="cuda")
+    lse = torch.full((10, 8), 7.0, device="cuda")
+    with pytest.raises(medha.MedhaError) as e:       # page table too short
+        medha.chunked_prefill_attn(b.q, b.k_pool, b.v_pool, pt, [0, 3], [100], [10], b.scale,
+                                   out, lse)
+    assert e.value.code == -1
+    with pytest.raises(medha.MedhaError) as e:       # chunk_len 0
+        medha.chunked_prefill_attn(b.q[:0], b.k_pool, b.v_pool, pt, b.page_table_offs, [100], [0],
+                                   b.scale, out[:0], lse[:0])
+    assert e.value.code == -1
+    with pytest.raises(medha.MedhaError) as e:       # heads not divisible
+        medha.chunked_prefill_attn(b.q[:, :7].contiguous(), b.k_pool, b.v_pool, pt,
+                                   b.page_table_offs, [100], [10], b.scale,
+                                   out[:, :7].contiguous(), lse[:, :7].contiguous())
+    assert e.value.code == -1
+    k32 = b.k_pool[..., :32].contiguous()
+    with pytest.raises(medha.MedhaError) as e:       # unsupported head_dim
+        medha.chunked_prefill_attn(b.q[..., :32].contiguous(), k32, k32, pt, b.page_table_offs,
+                                   [100], [10], b.scale)
+    assert e.value.code == -2
+    # a split plan without enough workspace
+    big = to_dev(wl.make_prefill_batch("w", 8, 1, 128, [20000], [64], seed=2))
+    need = medha.chunked_prefill_workspace_bytes(big.prefix_len, big.chunk_len, 8, 1, 128)
+    assert need > 256
+    with pytest.raises(medha.MedhaError) as e:
+        medha.chunked_prefill_attn(big.q, big.k_pool, big.v_pool,
+                                   torch.from_numpy(big.page_table).cuda(), big.page_table_offs,
+                                   big.prefix_len, big.chunk_len, big.scale,
+                                   workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == -3
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all()) and bool((lse == 7.0).all())
