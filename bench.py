@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged-attention hot path on one MI355X.
+
+A step is one call of the chunked-prefill entry point on the Llama-3-8B-shaped
+single-layer workload (32 q heads / 8 kv heads, d 128, prefix 32768 + chunk
+2048, 16-token pages, shuffled page table) with every input resident in HBM.
+`value` is algorithmic attention TFLOP/s (4*d*h_q flop per visible query-key
+pair, exact causal count) = flops per step / mean step time.
+
+The same JSON line also carries, each measured in its own timed loop:
+  decode   the KV-cache-parallel decode workload (1M-token context as 4 shards
+           of 262,144 through the decode-partial entry point, then the LSE
+           merge): KV-read GB/s against the HBM roofline;
+  sweep    the Llama-3-70B tensor-parallel share (8 q / 1 kv head, 1M prefix)
+           at chunk sizes 512..8192: TFLOP/s per chunk size;
+  mixed    one 1024-token prefill chunk at a 524,288-token prefix plus 64
+           decodes in one call.
+and `cpu_baseline`: the fp64 CPU oracle timed on a bounded sample of rows of
+the headline workload on this machine's host cores (a reported baseline only).
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--sections main,decode,sweep,mixed]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_calls(fn, steps, warmup):
+    """Mean / min milliseconds per call from HIP events recorded on torch's
+    current stream (the stream the library launches on), plus wall time."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(steps)]
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    per = np.array([a.elapsed_time(b) for a, b in ev])
+    return {"wall_ms_per_step": wall_ms / steps, "event_ms_mean": float(per.mean()),
+            "event_ms_min": float(per.min()), "event_ms_median": float(np.median(per))}
+
+
+def prefill_runner(batch):
+    import torch
+    import paper_2409_17264_amd as medha
+    pt = torch.from_numpy(batch.page_table).cuda()
+    out = torch.empty((batch.tokens, batch.h_q, batch.d), dtype=torch.float32, device="cuda")
+    lse = torch.empty((batch.tokens, batch.h_q), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(256, medha.chunked_prefill_workspace_bytes(
+        batch.prefix_len, batch.chunk_len, batch.h_q, batch.h_kv, batch.d)),
+        dtype=torch.uint8, device="cuda")
+
+    def run():
+        medha.chunked_prefill_attn(batch.q, batch.k_pool, batch.v_pool, pt, batch.page_table_offs,
+                                   batch.prefix_len, batch.chunk_len, batch.scale, out, lse, ws)
+    return run, out, lse
+
+
+def traffic_from_profile(name):
+    """HBM bytes per launch recorded in profiles/<name> by a rocprofv3 --pmc run
+    (line 'hbm_bytes_per_launch = N'), or None."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        for line in open(path):
+            if line.strip().startswith("hbm_bytes_per_launch"):
+                return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(batch, budget_s=15.0):
+    """The oracle, as it stands, on a seeded sample of rows of the same workload."""
+    import oracle
+    from paper_2409_17264_amd import workloads as wl
+    q, k, v = wl.bf16_bits(batch.q), wl.bf16_bits(batch.k_pool), wl.bf16_bits(batch.v_pool)
+    per_row = lambda rows: sum(4.0 * batch.d * batch.h_q * (int(batch.prefix_len[0]) + int(r) + 1)
+                               for r in rows)
+    rng = np.random.Generator(np.random.PCG64(99))
+    probe = np.sort(rng.choice(batch.tokens, size=4, replace=False)).astype(np.int64)
+    t0 = time.perf_counter()
+    oracle.chunked_prefill_attn(q, k, v, batch.page_table, batch.page_table_offs, batch.prefix_len,
+                                batch.chunk_len, batch.scale, probe)
+    t_probe = time.perf_counter() - t0
+    n = int(max(8, min(batch.tokens, budget_s / max(t_probe / 4, 1e-6))))
+    rows = np.sort(rng.choice(batch.tokens, size=n, replace=False)).astype(np.int64)
+    t0 = time.perf_counter()
+    oracle.chunked_prefill_attn(q, k, v, batch.page_table, batch.page_table_offs, batch.prefix_len,
+                                batch.chunk_len, batch.scale, rows)
+    dt = time.perf_counter() - t0
+    return {"value": per_row(rows) / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": dt,
+            "sample": f"{n} seeded random token rows x {batch.h_q} heads of the same workload "
+                      f"(fp64, two-pass softmax)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--sections", default="main,decode,sweep,mixed,cpu")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (KV-cache parallelism is exercised "
+                 "as several KV shards on the same GPU); run with --gpus 1")
+    sections = set(args.sections.split(","))
+
+    import torch
+    import paper_2409_17264_amd as medha
+    from paper_2409_17264_amd import workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    medha.load_library()
+    props = torch.cuda.get_device_properties(0)
+    log(f"device: {props.name} CUs={props.multi_processor_count} "
+        f"mem={props.total_memory / 2**30:.0f} GiB")
+
+    result = {}
+    # ------------------------------------------------------------- headline
+    b = wl.config2_llama8b("cuda:0")
+    run, out, lse = prefill_runner(b)
+    t = time_calls(run, args.steps, args.warmup)
+    flops = b.algorithmic_flops()
+    ms = t["wall_ms_per_step"]
+    tflops = flops / (ms * 1e-3) / 1e12
+    kern_tflops = flops / (t["event_ms_mean"] * 1e-3) / 1e12
+    log(f"main: {ms:.4f} ms/step wall, {t['event_ms_mean']:.4f} ms events -> {tflops:.1f} TFLOP/s")
+    result.update({
+        "metric": "chunked-prefill attn TFLOP/s + decode KV-read GB/s, % of MI355X roofline",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg2 Llama-3-8B layer chunked prefill: 32 q / 8 kv heads, d 128, "
+                               "prefix 32768 + chunk 2048, page 16, shuffled 2176-page table",
+                   "algorithmic_flops": flops, "kv_bytes": b.algorithmic_kv_bytes()},
+        "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": kern_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": traffic_from_profile("attn_kernel_cfg2_pmc.txt"),
+                     "kernel": "attn_kernel<128,2,false>", "event_ms_mean": t["event_ms_mean"],
+                     "event_ms_min": t["event_ms_min"]},
+    })
+    if "cpu" in sections:
+        result["cpu_baseline"] = cpu_baseline(b)
+        log(f"cpu oracle: {result['cpu_baseline']}")
+    del b, run, out, lse
+    torch.cuda.empty_cache()
+
+    # --------------------------------------------------------------- decode
+    if "decode" in sections:
+        c = wl.config3_kvp_decode("cuda:0")
+        pt = torch.from_numpy(c.page_table).cuda()
+        shards = len(c.shard_len)
+        po = torch.empty((shards, c.h_q, c.d), dtype=torch.float32, device="cuda")
+        pl = torch.empty((shards, c.h_q), dtype=torch.float32, device="cuda")
+        o = torch.empty((1, c.h_q, c.d), dtype=torch.float32, device="cuda")
+        l = torch.empty((1, c.h_q), dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(256, medha.decode_partial_workspace_bytes(c.shard_len, c.h_q, c.h_kv,
+                                                                      c.d)),
+                         dtype=torch.uint8, device="cuda")
+
+        def run_decode():
+            medha.decode_partial_attn(c.q, c.k_pool, c.v_pool, pt, c.shard_offs, c.q_index,
+                                      c.shard_len, c.scale, po, pl, ws)
+            medha.lse_merge(po.view(shards, 1, c.h_q, c.d), pl.view(shards, 1, c.h_q), o, l)
+        t = time_calls(run_decode, args.steps, args.warmup)
+        gbps = c.algorithmic_kv_bytes() / (t["event_ms_mean"] * 1e-3) / 1e9
+        log(f"decode: {t['event_ms_mean']:.4f} ms -> {gbps:.0f} GB/s")
+        result["decode"] = {
+            "workload": "cfg3 KVP decode: 1 query, 32 q / 8 kv heads, d 128, 1,048,576-token "
+                        "context as 4 shards of 262,144 + LSE merge",
+            "ms": t["event_ms_mean"], "ms_min": t["event_ms_min"], "value": gbps, "unit": "GB/s",
+            "kv_bytes": c.algorithmic_kv_bytes(),
+            "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                         "frac": gbps / PEAK_HBM_GBPS,
+                         "traffic": traffic_from_profile("attn_kernel_cfg3_pmc.txt"),
+                         "kernel": "attn_kernel<128,1,true> + split merge + lse_merge"}}
+        del c, pt, po, pl, ws
+        torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- sweep
+    if "sweep" in sections:
+        sweep = []
+        base = wl.config4_llama70b_tp(8192, "cuda:0")
+        for chunk in (512, 1024, 2048, 4096, 8192):
+            bb = wl.PrefillBatch(f"cfg4_c{chunk}", base.h_q, base.h_kv, base.d, base.prefix_len,
+                                 np.array([chunk], np.int32), base.page_table,
+                                 base.page_table_offs, base.num_pages,
+                                 base.q[:chunk].contiguous(), base.k_pool, base.v_pool, base.scale)
+            run, _, _ = prefill_runner(bb)
+            t = time_calls(run, max(3, args.steps // 3), 2)
+            tf = bb.algorithmic_flops() / (t["event_ms_mean"] * 1e-3) / 1e12
+            log(f"sweep c={chunk}: {t['event_ms_mean']:.3f} ms -> {tf:.1f} TFLOP/s")
+            sweep.append({"chunk": chunk, "ms": t["event_ms_mean"], "tflops": tf,
+                          "frac_of_peak": tf / PEAK_BF16_TFLOPS})
+        result["sweep"] = {"workload": "cfg4 Llama-3-70B TP8 share: 8 q / 1 kv head, d 128, "
+                                       "prefix 1,048,576", "points": sweep}
+        del base, bb, run
+        torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- mixed
+    if "mixed" in sections:
+        m = wl.config5_mixed("cuda:0")
+        run, _, _ = prefill_runner(m)
+        t = time_calls(run, max(3, args.steps // 3), 2)
+        pf = 4.0 * m.d * m.h_q * (1024.0 * 524288 + 1024 * 1025 / 2)
+        dec_bytes = 4.0 * m.d * m.h_kv * float(m.meta["decode_lens"].sum())
+        log(f"mixed: {t['event_ms_mean']:.3f} ms")
+        result["mixed"] = {
+            "workload": "cfg5: prefill chunk 1024 @ prefix 524,288 + 64 decodes "
+                        "(log-normal lengths, median 2048, sigma 1.0, clip [256,16384]), one call",
+            "ms": t["event_ms_mean"], "prefill_flops": pf, "decode_kv_bytes": dec_bytes,
+            "tflops_whole_call": (pf + 4.0 * m.d * m.h_q * float(m.meta["decode_lens"].sum()))
+            / (t["event_ms_mean"] * 1e-3) / 1e12}
+        del m, run
+        torch.cuda.empty_cache()
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

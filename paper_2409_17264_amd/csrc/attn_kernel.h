@@ -245,15 +245,19 @@ __global__ void __launch_bounds__(kThreads) attn_kernel(const AttnArgs args) {
   const SeqDesc* descs = args.descs ? args.descs : args.inline_descs;
   const SeqDesc sd = descs[find_seq(descs, args.n_seq, blockIdx.x)];
 
-  // Slot -> (KV head, KV split, row tile).  Slot s runs on die s % 8; all row
-  // tiles that stream the same (KV head, split) get the same die, so its L2
-  // serves the K/V re-reads of that group.
+  // Slot -> (KV head, KV split, row tile).  Slot s runs on die s % 8.  The
+  // sequence's work items, ordered (group, row tile) with group = (split, KV
+  // head), are cut into 8 equal contiguous runs, one per die: the row tiles that
+  // stream the same K/V range share a die and hence its L2.
   const int u = blockIdx.x - sd.work_start;
   const int groups = args.h_kv * sd.n_split;
+  const int items = groups * sd.n_row_tiles;
+  const int per_die = (items + kXcds - 1) / kXcds;
   const int y = u / kXcds;
-  const int grp = (u % kXcds) + kXcds * (y / sd.n_row_tiles);
-  const int row_tile = y % sd.n_row_tiles;
-  if (grp >= groups) return;
+  const int item = (u % kXcds) * per_die + y;
+  if (y >= per_die || item >= items) return;
+  const int grp = item / sd.n_row_tiles;
+  const int row_tile = item % sd.n_row_tiles;
   const int kv_head = grp % args.h_kv;
   const int split = grp / args.h_kv;
 

@@ -19,6 +19,7 @@ constexpr int kPageSize = 16;     // tokens per KV page
 constexpr int kThreads = 256;     // threads per workgroup (4 wavefronts of 64)
 constexpr int kWaves = 4;
 constexpr int kXcds = 8;          // accelerator dies; workgroup i is dispatched to die i % 8
+constexpr int kPrefillStages = 3;  // K/V tiles in flight per workgroup (LDS ring)
 constexpr int kMaxInlineSeq = 64; // sequence descriptors that travel as kernel arguments
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -27,7 +28,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 // [0, prefix_len + j] of the paged sequence whose page table starts at pt_off.
 // A decode item is chunk_len == 1 with prefix_len == kv_len - 1 (so -1 means
 // "no keys").  The sequence owns workgroup slots
-// [work_start, work_start + 8 * ceil(h_kv * n_split / 8) * n_row_tiles).
+// [work_start, work_start + 8 * ceil(h_kv * n_split * n_row_tiles / 8)).
 struct SeqDesc {
   int64_t pt_off;           // first entry of the sequence in the page table
   int32_t q_row;            // first query token row in q

@@ -12,6 +12,7 @@
 #include "common.h"
 #include "merge_kernel.h"
 #include "planner.h"
+#include "prefill_kernel.h"
 
 namespace medha {
 namespace {
@@ -41,6 +42,13 @@ hipError_t launch_attn(const AttnArgs& a, int grid, hipStream_t stream) {
   return hipGetLastError();
 }
 
+template <int D, int NW>
+hipError_t launch_prefill(const AttnArgs& a, int grid, hipStream_t stream) {
+  hipLaunchKernelGGL((prefill_kernel<D, NW, kPrefillStages>), dim3(grid), dim3(NW * 64), 0,
+                     stream, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_plan(const LaunchPlan& lp, bool split_keys, int d, AttnArgs& a,
                        void* descs_dev, hipStream_t stream) {
   if (lp.descs.empty() || lp.n_slots == 0) return hipSuccess;
@@ -60,11 +68,11 @@ hipError_t launch_plan(const LaunchPlan& lp, bool split_keys, int d, AttnArgs& a
     e = d == 128 ? launch_attn<128, 1, true>(a, lp.n_slots, stream)
                  : launch_attn<64, 1, true>(a, lp.n_slots, stream);
   } else if (lp.q_blocks == 2) {
-    e = d == 128 ? launch_attn<128, 2, false>(a, lp.n_slots, stream)
-                 : launch_attn<64, 2, false>(a, lp.n_slots, stream);
+    e = d == 128 ? launch_prefill<128, 8>(a, lp.n_slots, stream)
+                 : launch_prefill<64, 8>(a, lp.n_slots, stream);
   } else {
-    e = d == 128 ? launch_attn<128, 1, false>(a, lp.n_slots, stream)
-                 : launch_attn<64, 1, false>(a, lp.n_slots, stream);
+    e = d == 128 ? launch_prefill<128, 4>(a, lp.n_slots, stream)
+                 : launch_prefill<64, 4>(a, lp.n_slots, stream);
   }
   if (e != hipSuccess || !lp.any_split) return e;
 

@@ -78,8 +78,8 @@ inline void plan_launch(LaunchPlan& lp, int h_kv, int gqa, int target_wgs, int m
       part_rows += n_split * sd.chunk_len;
       lp.any_split = true;
     }
-    const int64_t groups = (int64_t)h_kv * n_split;
-    slot += (int)(kXcds * ceil_div(groups, kXcds) * sd.n_row_tiles);
+    const int64_t items = (int64_t)h_kv * n_split * sd.n_row_tiles;
+    slot += (int)(kXcds * ceil_div(items, kXcds));
     rank += sd.chunk_len;
   }
   lp.n_slots = slot;
