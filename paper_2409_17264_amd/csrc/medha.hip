@@ -8,8 +8,8 @@
 #include <cstring>
 #include <vector>
 
-#include "attn_kernel.h"
 #include "common.h"
+#include "decode_kernel.h"
 #include "merge_kernel.h"
 #include "planner.h"
 #include "prefill_kernel.h"
@@ -36,9 +36,9 @@ int check_heads(int h_q, int h_kv, int d, int page_size) {
   return MEDHA_OK;
 }
 
-template <int D, int QB, bool SPLIT_KEYS>
-hipError_t launch_attn(const AttnArgs& a, int grid, hipStream_t stream) {
-  hipLaunchKernelGGL((attn_kernel<D, QB, SPLIT_KEYS>), dim3(grid), dim3(kThreads), 0, stream, a);
+template <int D>
+hipError_t launch_decode(const AttnArgs& a, int grid, hipStream_t stream) {
+  hipLaunchKernelGGL((decode_kernel<D>), dim3(grid), dim3(kThreads), 0, stream, a);
   return hipGetLastError();
 }
 
@@ -65,8 +65,8 @@ hipError_t launch_plan(const LaunchPlan& lp, bool split_keys, int d, AttnArgs& a
   }
   hipError_t e;
   if (split_keys) {
-    e = d == 128 ? launch_attn<128, 1, true>(a, lp.n_slots, stream)
-                 : launch_attn<64, 1, true>(a, lp.n_slots, stream);
+    e = d == 128 ? launch_decode<128>(a, lp.n_slots, stream)
+                 : launch_decode<64>(a, lp.n_slots, stream);
   } else if (lp.q_blocks == 2) {
     e = d == 128 ? launch_prefill<128, 8>(a, lp.n_slots, stream)
                  : launch_prefill<64, 8>(a, lp.n_slots, stream);

@@ -152,12 +152,12 @@ struct RowBlock {
     }
   }
 
-  // One 64-key tile.  key0 = sequence index of the tile's first key.
-  template <bool MASK>
+  // One tile of NKB blocks of 32 keys.  key0 = sequence index of the tile's first key.
+  template <int NKB, bool MASK>
   __device__ __forceinline__ void step(const char* k_lds, const char* v_lds, int key0, int half) {
-    f32x16 s[2];
+    f32x16 s[NKB];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < NKB; ++kb) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
 #pragma unroll
@@ -171,7 +171,7 @@ struct RowBlock {
 
     float mx = -INFINITY;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         if (MASK) {
@@ -195,10 +195,10 @@ struct RowBlock {
     }
     m = m_new;
 
-    bf16x8 p[2][2];
+    bf16x8 p[NKB][2];
     float ls = 0.f;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < NKB; ++kb) {
       f32x8 lo, hi;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
@@ -220,7 +220,7 @@ struct RowBlock {
 #pragma unroll
     for (int db = 0; db < kDBlocks; ++db) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+      for (int kb = 0; kb < NKB; ++kb) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           const char* vp = v_lds + (kb * 32 + 16 * t) * (D * 2) + v_off[db];
@@ -314,7 +314,7 @@ __device__ __forceinline__ void run_tiles(RowBlock<D>& rb, const AttnArgs& args,
                           nxt + G::kTileBytes, wave, lane);
         page_next = tile_page<D, NW>(pt, min(cur + NS, last), kv_total, wave);
         const char* st = ring.base + s * kStage;
-        rb.template step<MASK>(st, st + G::kTileBytes, cur * G::kTileKeys, half);
+        rb.template step<2, MASK>(st, st + G::kTileBytes, cur * G::kTileKeys, half);
       }
     }
   }
