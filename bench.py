@@ -18,7 +18,8 @@ The same JSON line also carries, each measured in its own timed loop:
 and `cpu_baseline`: the fp64 CPU oracle timed on a bounded sample of rows of
 the headline workload on this machine's host cores (a reported baseline only).
 
-Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--sections main,decode,sweep,mixed]
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W]
+                [--sections main,decode,sweep,mixed,cpu[,copy]]
 """
 import argparse
 import json
@@ -137,6 +138,16 @@ def main():
         f"mem={props.total_memory / 2**30:.0f} GiB")
 
     result = {}
+    if "copy" in sections:
+        # plain device-to-device copy of known size: the yardstick that scales the
+        # FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        t = time_calls(lambda: dst.copy_(src), 3, 1)
+        log(f"copy 1 GiB: {t['event_ms_mean']:.3f} ms -> "
+            f"{2 * src.numel() / (t['event_ms_mean'] * 1e-3) / 1e9:.0f} GB/s read+write")
+        del src, dst
+        torch.cuda.empty_cache()
     # ------------------------------------------------------------- headline
     b = wl.config2_llama8b("cuda:0")
     run, out, lse = prefill_runner(b)
@@ -156,8 +167,8 @@ def main():
                    "algorithmic_flops": flops, "kv_bytes": b.algorithmic_kv_bytes()},
         "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": kern_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": traffic_from_profile("attn_kernel_cfg2_pmc.txt"),
-                     "kernel": "attn_kernel<128,2,false>", "event_ms_mean": t["event_ms_mean"],
+                     "traffic": traffic_from_profile("prefill_kernel_cfg2_pmc.txt"),
+                     "kernel": "prefill_kernel<128,8,3>", "event_ms_mean": t["event_ms_mean"],
                      "event_ms_min": t["event_ms_min"]},
     })
     if "cpu" in sections:
@@ -193,8 +204,8 @@ def main():
             "kv_bytes": c.algorithmic_kv_bytes(),
             "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                          "frac": gbps / PEAK_HBM_GBPS,
-                         "traffic": traffic_from_profile("attn_kernel_cfg3_pmc.txt"),
-                         "kernel": "attn_kernel<128,1,true> + split merge + lse_merge"}}
+                         "traffic": traffic_from_profile("decode_kernel_cfg3_pmc.txt"),
+                         "kernel": "decode_kernel<128> (+ split_merge_kernel, lse_merge_kernel)"}}
         del c, pt, po, pl, ws
         torch.cuda.empty_cache()
 

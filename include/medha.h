@@ -149,6 +149,36 @@ int medha_lse_merge(const float* out_partial, const float* lse_partial, int32_t 
                     int64_t rows, int32_t num_q_heads, int32_t head_dim, float* out, float* lse,
                     void* hip_stream);
 
+/*
+ * Introspection of the launch plan (host only; needs no GPU).  How the library
+ * would lay a chunked-prefill batch out over workgroups on a device with
+ * num_cus compute units (0 = the current device, or 256 if there is none):
+ * per sequence the kernel it goes to, its query-row tiling and its KV split.
+ * A decode item of kv_len n is the sequence (prefix_len n - 1, chunk_len 1),
+ * so prefix_len may be -1 here.  medha_describe_slot maps a workgroup slot of
+ * a sequence (0 <= slot < n_slots) to its work item and returns 1, or 0 for an
+ * idle padding slot.  These two calls exist for tests and tuning; they launch
+ * nothing.
+ */
+typedef struct medha_plan_entry {
+  int32_t mode;            /* 0: row-split prefill kernel, 1: key-split decode kernel */
+  int32_t rows_per_wg;     /* (token, head-in-group) query rows per workgroup          */
+  int32_t tile_keys;       /* granule of the KV split, in keys                         */
+  int32_t n_row_tiles;     /* row tiles per KV head                                    */
+  int32_t n_split;         /* KV ranges; > 1 means partials + merge                    */
+  int32_t tiles_per_split; /* granules per range                                       */
+  int32_t work_start;      /* first workgroup slot inside its kernel launch            */
+  int32_t n_slots;         /* slots owned: 8 * ceil(kv_heads * n_split * n_row_tiles / 8) */
+} medha_plan_entry;
+
+int medha_describe_plan(const int32_t* prefix_len, const int32_t* chunk_len, int32_t batch,
+                        int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim,
+                        int32_t num_cus, medha_plan_entry* entries /* host [batch] */,
+                        int32_t* grid_rows, int32_t* grid_keys, size_t* workspace_bytes);
+
+int medha_describe_slot(int32_t slot, int32_t num_kv_heads, int32_t n_split, int32_t n_row_tiles,
+                        int32_t* kv_head, int32_t* split, int32_t* row_tile);
+
 /* Static, human-readable text for a return code. */
 const char* medha_strerror(int code);
 

@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     chunked_prefill_workspace_bytes,
     decode_partial_attn,
     decode_partial_workspace_bytes,
+    describe_plan,
+    describe_slot,
     library_path,
     load_library,
     lse_merge,

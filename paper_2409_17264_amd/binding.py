@@ -23,6 +23,8 @@ EXPORTS = (
     "medha_decode_partial_attn",
     "medha_decode_partial_workspace_bytes",
     "medha_lse_merge",
+    "medha_describe_plan",
+    "medha_describe_slot",
     "medha_strerror",
     "medha_abi_version",
 )
@@ -32,6 +34,12 @@ class MedhaError(RuntimeError):
     def __init__(self, code: int, text: str):
         super().__init__(f"medha error {code}: {text}")
         self.code = code
+
+
+class PlanEntry(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("mode", "rows_per_wg", "tile_keys", "n_row_tiles",
+                                              "n_split", "tiles_per_split", "work_start",
+                                              "n_slots")]
 
 
 class _KvCache(ctypes.Structure):
@@ -68,6 +76,13 @@ def load_library():
     lib.medha_decode_partial_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
     lib.medha_lse_merge.restype = ctypes.c_int
     lib.medha_lse_merge.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp]
+    lib.medha_describe_plan.restype = ctypes.c_int
+    lib.medha_describe_plan.argtypes = [vp, vp, i32, i32, i32, i32, i32, ctypes.POINTER(PlanEntry),
+                                        ctypes.POINTER(i32), ctypes.POINTER(i32),
+                                        ctypes.POINTER(sz)]
+    lib.medha_describe_slot.restype = ctypes.c_int
+    lib.medha_describe_slot.argtypes = [i32, i32, i32, i32, ctypes.POINTER(i32),
+                                        ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.medha_strerror.restype = ctypes.c_char_p
     lib.medha_strerror.argtypes = [ctypes.c_int]
     lib.medha_abi_version.restype = ctypes.c_int
@@ -116,6 +131,30 @@ def decode_partial_workspace_bytes(kv_len, num_q_heads: int, num_kv_heads: int,
     kl = _host(kv_len, np.int32)
     return int(load_library().medha_decode_partial_workspace_bytes(
         _hp(kl), len(kl), num_q_heads, num_kv_heads, head_dim))
+
+
+def describe_plan(prefix_len, chunk_len, num_q_heads: int, num_kv_heads: int, head_dim: int,
+                  num_cus: int = 0):
+    """Host-only: (entries, grid_rows, grid_keys, workspace_bytes) of the launch plan."""
+    lib = load_library()
+    pre, chk = _host(prefix_len, np.int32), _host(chunk_len, np.int32)
+    entries = (PlanEntry * max(1, len(pre)))()
+    g_rows, g_keys, ws = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_size_t(0)
+    _check(lib.medha_describe_plan(_hp(pre), _hp(chk), len(pre), num_q_heads, num_kv_heads,
+                                   head_dim, num_cus, entries, ctypes.byref(g_rows),
+                                   ctypes.byref(g_keys), ctypes.byref(ws)))
+    return list(entries)[:len(pre)], g_rows.value, g_keys.value, ws.value
+
+
+def describe_slot(slot: int, num_kv_heads: int, n_split: int, n_row_tiles: int):
+    """Host-only: (kv_head, split, row_tile) of a workgroup slot, or None if idle."""
+    lib = load_library()
+    h, s, r = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = lib.medha_describe_slot(slot, num_kv_heads, n_split, n_row_tiles, ctypes.byref(h),
+                                 ctypes.byref(s), ctypes.byref(r))
+    if rc < 0:
+        _check(rc)
+    return (h.value, s.value, r.value) if rc == 1 else None
 
 
 def _workspace(nbytes: int, device) -> torch.Tensor:

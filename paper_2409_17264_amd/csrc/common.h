@@ -80,6 +80,28 @@ struct MergeArgs {
 };
 static_assert(sizeof(MergeArgs) <= 4096, "kernel argument block too large");
 
+// Workgroup slot u of a sequence -> its work item.  Slot u runs on die u % 8
+// (the hardware deals consecutive workgroups round-robin to the 8 dies).  The
+// sequence's items, ordered (group, row tile) with group = (KV split, KV head),
+// are cut into 8 equal contiguous runs, one per die: the row tiles that stream
+// the same K/V range share a die and hence its L2.  Slots past a run are idle.
+struct SlotItem {
+  int valid, kv_head, split, row_tile;
+};
+__host__ __device__ inline SlotItem decode_slot(int u, int h_kv, int n_split, int n_row_tiles) {
+  const int items = h_kv * n_split * n_row_tiles;
+  const int per_die = (items + kXcds - 1) / kXcds;
+  const int y = u / kXcds;
+  const int item = (u % kXcds) * per_die + y;
+  SlotItem r;
+  r.valid = (y < per_die && item < items) ? 1 : 0;
+  const int grp = item / n_row_tiles;
+  r.row_tile = item % n_row_tiles;
+  r.kv_head = grp % h_kv;
+  r.split = grp / h_kv;
+  return r;
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 

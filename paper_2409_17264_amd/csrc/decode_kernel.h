@@ -75,14 +75,9 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const AttnArgs args) {
   const SeqDesc* descs = args.descs ? args.descs : args.inline_descs;
   const SeqDesc sd = uniform(descs[find_seq_slot(descs, args.n_seq, blockIdx.x)]);
   // one row tile per sequence here, so a slot is just (KV head, split)
-  const int u = blockIdx.x - sd.work_start;
-  const int groups = args.h_kv * sd.n_split;
-  const int per_die = (groups + kXcds - 1) / kXcds;
-  const int y = u / kXcds;
-  const int grp = (u % kXcds) * per_die + y;
-  if (y >= per_die || grp >= groups) return;
-  const int kv_head = grp % args.h_kv;
-  const int split = grp / args.h_kv;
+  const SlotItem it = decode_slot(blockIdx.x - sd.work_start, args.h_kv, sd.n_split, 1);
+  if (!it.valid) return;
+  const int kv_head = it.kv_head, split = it.split;
 
   const int gqa = args.h_q / args.h_kv;
   const int n_rows = sd.chunk_len * gqa;  // <= 32

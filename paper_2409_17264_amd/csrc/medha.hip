@@ -249,6 +249,57 @@ int medha_decode_partial_attn(const void* q, int32_t num_queries, const medha_kv
                   workspace, workspace_bytes, hip_stream);
 }
 
+int medha_describe_plan(const int32_t* prefix_len, const int32_t* chunk_len, int32_t batch,
+                        int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim,
+                        int32_t num_cus, medha_plan_entry* entries, int32_t* grid_rows,
+                        int32_t* grid_keys, size_t* workspace_bytes) {
+  if (batch < 0 || (batch > 0 && (prefix_len == nullptr || chunk_len == nullptr ||
+                                  entries == nullptr)))
+    return MEDHA_ERR_INVALID_ARG;
+  int rc = check_heads(num_q_heads, num_kv_heads, head_dim, kPageSize);
+  if (rc != MEDHA_OK) return rc;
+  std::vector<SeqInput> seqs(batch);
+  int64_t row = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (prefix_len[b] < -1 || chunk_len[b] < 1) return MEDHA_ERR_INVALID_ARG;
+    seqs[b] = SeqInput{0, (int32_t)row, (int32_t)row, chunk_len[b], prefix_len[b]};
+    row += chunk_len[b];
+  }
+  const Plan plan = make_plan(seqs.data(), batch, num_q_heads, num_kv_heads, head_dim,
+                              num_cus > 0 ? num_cus : current_num_cus());
+  for (int mode = 0; mode < 2; ++mode) {
+    const LaunchPlan& lp = mode == 0 ? plan.rows : plan.keys;
+    for (size_t i = 0; i < lp.descs.size(); ++i) {
+      const SeqDesc& sd = lp.descs[i];
+      medha_plan_entry& e = entries[lp.seq_index[i]];
+      e.mode = mode;
+      e.rows_per_wg = lp.shape.rows_per_wg;
+      e.tile_keys = lp.shape.tile_keys;
+      e.n_row_tiles = sd.n_row_tiles;
+      e.n_split = sd.n_split;
+      e.tiles_per_split = sd.tiles_per_split;
+      e.work_start = sd.work_start;
+      e.n_slots = (i + 1 < lp.descs.size() ? lp.descs[i + 1].work_start : lp.n_slots) -
+                  sd.work_start;
+    }
+  }
+  if (grid_rows) *grid_rows = plan.rows.n_slots;
+  if (grid_keys) *grid_keys = plan.keys.n_slots;
+  if (workspace_bytes) *workspace_bytes = plan.bytes;
+  return MEDHA_OK;
+}
+
+int medha_describe_slot(int32_t slot, int32_t num_kv_heads, int32_t n_split, int32_t n_row_tiles,
+                        int32_t* kv_head, int32_t* split, int32_t* row_tile) {
+  if (slot < 0 || num_kv_heads <= 0 || n_split <= 0 || n_row_tiles <= 0)
+    return MEDHA_ERR_INVALID_ARG;
+  const SlotItem it = decode_slot(slot, num_kv_heads, n_split, n_row_tiles);
+  if (kv_head) *kv_head = it.kv_head;
+  if (split) *split = it.split;
+  if (row_tile) *row_tile = it.row_tile;
+  return it.valid;
+}
+
 int medha_lse_merge(const float* out_partial, const float* lse_partial, int32_t num_splits,
                     int64_t rows, int32_t num_q_heads, int32_t head_dim, float* out, float* lse,
                     void* hip_stream) {

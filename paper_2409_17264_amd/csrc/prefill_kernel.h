@@ -330,20 +330,10 @@ __global__ void __launch_bounds__(NW * 64) prefill_kernel(const AttnArgs args) {
   const SeqDesc* descs = args.descs ? args.descs : args.inline_descs;
   const SeqDesc sd = uniform(descs[find_seq_slot(descs, args.n_seq, blockIdx.x)]);
 
-  // Slot -> (KV head, KV split, row tile); see the planner.  Slot s runs on die
-  // s % 8 and the sequence's items, ordered (group, row tile), are cut into 8
-  // contiguous runs, so row tiles streaming the same K/V range share a die's L2.
-  const int u = blockIdx.x - sd.work_start;
-  const int groups = args.h_kv * sd.n_split;
-  const int items = groups * sd.n_row_tiles;
-  const int per_die = (items + kXcds - 1) / kXcds;
-  const int y = u / kXcds;
-  const int item = (u % kXcds) * per_die + y;
-  if (y >= per_die || item >= items) return;
-  const int grp = item / sd.n_row_tiles;
-  const int row_tile = item % sd.n_row_tiles;
-  const int kv_head = grp % args.h_kv;
-  const int split = grp / args.h_kv;
+  const SlotItem it =
+      decode_slot(blockIdx.x - sd.work_start, args.h_kv, sd.n_split, sd.n_row_tiles);
+  if (!it.valid) return;
+  const int row_tile = it.row_tile, kv_head = it.kv_head, split = it.split;
 
   const int gqa = args.h_q / args.h_kv;
   const int n_rows = sd.chunk_len * gqa;
