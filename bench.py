@@ -44,20 +44,29 @@ def log(*a):
 def time_calls(fn, steps, warmup):
     """Mean / min milliseconds per call from HIP events recorded on torch's
     current stream (the stream the library launches on), plus wall time."""
+    import gc
     import torch
     for _ in range(warmup):
         fn()
-    torch.cuda.synchronize()
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
           for _ in range(steps)]
-    t0 = time.perf_counter()
-    for a, b in ev:
-        a.record()
-        fn()
-        b.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
+    # as timeit does: no cyclic-GC pause of the interpreter inside the timed region
+    gc.collect()
+    gc.disable()
+    try:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+    finally:
+        gc.enable()
     per = np.array([a.elapsed_time(b) for a, b in ev])
+    if os.environ.get("BENCH_DEBUG"):
+        log("per-step ms:", np.round(per, 3).tolist())
     return {"wall_ms_per_step": wall_ms / steps, "event_ms_mean": float(per.mean()),
             "event_ms_min": float(per.min()), "event_ms_median": float(np.median(per))}
 
@@ -119,8 +128,8 @@ def cpu_baseline(batch, budget_s=15.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--sections", default="main,decode,sweep,mixed,cpu")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -196,7 +205,8 @@ def main():
             medha.lse_merge(po.view(shards, 1, c.h_q, c.d), pl.view(shards, 1, c.h_q), o, l)
         t = time_calls(run_decode, args.steps, args.warmup)
         gbps = c.algorithmic_kv_bytes() / (t["event_ms_mean"] * 1e-3) / 1e9
-        log(f"decode: {t['event_ms_mean']:.4f} ms -> {gbps:.0f} GB/s")
+        log(f"decode: {t['event_ms_mean']:.4f} ms (min {t['event_ms_min']:.4f}, median "
+            f"{t['event_ms_median']:.4f}) -> {gbps:.0f} GB/s")
         result["decode"] = {
             "workload": "cfg3 KVP decode: 1 query, 32 q / 8 kv heads, d 128, 1,048,576-token "
                         "context as 4 shards of 262,144 + LSE merge",

@@ -17,6 +17,8 @@
 // the way of the memory stream.
 #pragma once
 
+#include <type_traits>
+
 #include "common.h"
 #include "prefill_kernel.h"
 
@@ -68,7 +70,11 @@ __device__ __forceinline__ void issue_block(const AttnArgs& args, int page0, int
 }
 
 template <int D>
-__global__ void __launch_bounds__(kThreads) decode_kernel(const AttnArgs args) {
+// (launched with 256 threads; the bound of 512 makes the compiler budget for two wavefronts
+// per SIMD, i.e. at most 256 vector registers, all architectural: with more it parks the
+// accumulators in AGPRs and copies them back and forth around every vector-ALU use)
+__global__ void __launch_bounds__(2 * kThreads)
+decode_kernel(const AttnArgs args) {
   using G = DecodeGeom<D>;
   __shared__ __attribute__((aligned(1024))) char lds[G::kLdsBytes];
 
@@ -125,34 +131,31 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const AttnArgs args) {
     const uint32_t base = ring_lds + st * G::kBlockBytes;
     issue_block<D>(args, page0, page1, key0, kv_total, kv_head, base, base + G::kHalfBytes, lane);
   };
-  auto compute = [&](int b, int st) {
-    const int key0 = k_begin + b * G::kBlockKeys;
-    const char* base = ring + st * G::kBlockBytes;
-    if (key0 + G::kBlockKeys <= unmasked_keys)
-      rb.template step<1, false>(base, base + G::kHalfBytes, key0, half);
-    else
-      rb.template step<1, true>(base, base + G::kHalfBytes, key0, half);
-  };
-
-  // Blocks of this wavefront: wave, wave + 4, ...  Two are in flight at any time.
-  int b = wave;
-  if (b < n_blocks) issue(b, 0);
-  if (b + kWaves < n_blocks) issue(b + kWaves, 1);
-  for (; b < n_blocks; b += 2 * kWaves) {
-#pragma unroll
-    for (int st = 0; st < 2; ++st) {
-      const int cur = b + st * kWaves;
-      if (cur < n_blocks) {
-        if (cur + kWaves < n_blocks)
-          wait_vmcnt<G::kLoadsPerBlock>();  // the younger block may still fly
-        else
-          wait_vmcnt<0>();
-        compute(cur, st);
-        // every LDS read of the stage has returned (its data fed the matrix cores)
-        if (cur + 2 * kWaves < n_blocks) issue(cur + 2 * kWaves, st);
-      }
+  // Walks this wavefront's blocks b0, b0+4, ... < b_end with two in flight.
+  // Self-contained: starts and ends with no load in flight.  MASK applies the
+  // per-row key limit (only the last blocks of a sequence need it).
+  auto run_blocks = [&](int b0, int b_end, auto mask_tag) {
+    constexpr bool MASK = decltype(mask_tag)::value;
+    if (b0 < b_end) issue(b0, 0);
+    if (b0 + kWaves < b_end) issue(b0 + kWaves, 1);
+    int st = 0;
+    for (int b = b0; b < b_end; b += kWaves, st ^= 1) {
+      if (b + kWaves < b_end)
+        wait_vmcnt<G::kLoadsPerBlock>();  // the younger block may still fly
+      else
+        wait_vmcnt<0>();
+      const char* base = ring + st * G::kBlockBytes;
+      rb.template step<1, MASK>(base, base + G::kHalfBytes, k_begin + b * G::kBlockKeys, half);
+      // every LDS read of the stage has returned (its data fed the matrix cores)
+      if (b + 2 * kWaves < b_end) issue(b + 2 * kWaves, st);
     }
-  }
+  };
+  // blocks below n_unmasked are visible to every row; this wavefront's first block at or
+  // above it is the smallest wave + 4i >= n_unmasked
+  const int n_unmasked = min(n_blocks, max(0, unmasked_keys - k_begin) / G::kBlockKeys);
+  const int first_masked = wave + ((max(0, n_unmasked - wave) + kWaves - 1) / kWaves) * kWaves;
+  run_blocks(wave, n_unmasked, std::false_type{});
+  run_blocks(first_masked, n_blocks, std::true_type{});
 
   // Combine the 4 wavefronts' (m, l, O) over their disjoint keys through LDS.
   const bool direct = sd.n_split == 1;

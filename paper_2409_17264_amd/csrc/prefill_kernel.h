@@ -152,20 +152,66 @@ struct RowBlock {
     }
   }
 
-  // One tile of NKB blocks of 32 keys.  key0 = sequence index of the tile's first key.
+  // V^T operands of 16-key slice g (keys 16g .. 16g+15 of the tile) for all D/32
+  // head-dim blocks: for this lane's half, keys 16g + 4*half + {0..3} and the
+  // same + 8, through the transposing LDS read of row-major V.
+  __device__ __forceinline__ void read_v_slice(const char* v_lds, int g,
+                                               bf16x8 (&vop)[kDBlocks]) const {
+    const char* vrow = v_lds + g * 16 * (D * 2);
+#pragma unroll
+    for (int db = 0; db < kDBlocks; ++db) {
+      const char* vp = vrow + v_off[db];
+      const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (s16x4 __attribute__((address_space(3)))*)(vp));
+      const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (s16x4 __attribute__((address_space(3)))*)(vp + 8 * (D * 2)));
+      vop[db] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+  }
+
+  // One tile of NKB blocks of 32 keys (2*NKB slices of 16 keys).  The instruction
+  // order is laid out by hand as a software pipeline, and fenced so that it
+  // stays that way: LDS operand reads are issued two steps before the MFMAs that
+  // consume them (their latency would otherwise stall every MFMA), and the
+  // exponentials of slice g+1 sit between the MFMAs of slice g.
+  //   S^T = K Q^T:    A = 32 keys x 16 dims from LDS, B = Q^T from registers.
+  //   softmax:        mask on diagonal tiles, row maximum (lane-local + one
+  //                   half-wave exchange), accumulator rescale only if some
+  //                   row's maximum moved, p = exp2(s*scale_log2 - m), row sum.
+  //   O^T += V^T P^T: B = P^T slice taken from the S^T registers of the same
+  //                   keys (bf16, round to nearest even), A = V^T slice.
+  // key0 = sequence index of the tile's first key.
   template <int NKB, bool MASK>
   __device__ __forceinline__ void step(const char* k_lds, const char* v_lds, int key0, int half) {
+    constexpr int kGroups = 2 * NKB;
+    bf16x8 vop[2][kDBlocks];
+    read_v_slice(v_lds, 0, vop[0]);
+    read_v_slice(v_lds, 1, vop[1]);
+
     f32x16 s[NKB];
+    {
+      bf16x8 a[3][NKB];
 #pragma unroll
-    for (int kb = 0; kb < NKB; ++kb) {
+      for (int kb = 0; kb < NKB; ++kb) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
+        for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
+        // rows kb*32 + col: the swizzle only looks at row bits below 32
+        a[0][kb] = *reinterpret_cast<const bf16x8*>(k_lds + kb * 32 * (D * 2) + k_off[0]);
+        a[1][kb] = *reinterpret_cast<const bf16x8*>(k_lds + kb * 32 * (D * 2) + k_off[1]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int sl = 0; sl < kSlices; ++sl) {
-        // rows kb*32 + col: the swizzle only looks at row bits below 32
-        const bf16x8 a =
-            *reinterpret_cast<const bf16x8*>(k_lds + kb * 32 * (D * 2) + k_off[sl]);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[sl], s[kb], 0, 0, 0);
+        if (sl + 2 < kSlices) {
+#pragma unroll
+          for (int kb = 0; kb < NKB; ++kb)
+            a[(sl + 2) % 3][kb] =
+                *reinterpret_cast<const bf16x8*>(k_lds + kb * 32 * (D * 2) + k_off[sl + 2]);
+        }
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[sl % 3][kb], q[sl], s[kb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
 
@@ -195,45 +241,33 @@ struct RowBlock {
     }
     m = m_new;
 
-    bf16x8 p[NKB][2];
     float ls = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < NKB; ++kb) {
-      f32x8 lo, hi;
+    // P^T operand of slice g: elements 8*(g%2) .. +7 of S^T block g/2
+    auto probs = [&](int g) -> bf16x8 {
+      f32x8 pe;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        lo[e] = fast_exp2(__builtin_fmaf(s[kb][e], scale_log2, -m_use));
-        hi[e] = fast_exp2(__builtin_fmaf(s[kb][8 + e], scale_log2, -m_use));
-        if (MASK) {  // also right when scale_log2 == 0 (then -inf * 0 is not a number)
-          lo[e] = (s[kb][e] == -INFINITY) ? 0.f : lo[e];
-          hi[e] = (s[kb][8 + e] == -INFINITY) ? 0.f : hi[e];
-        }
-        ls += lo[e] + hi[e];
+        const float sv = s[g >> 1][8 * (g & 1) + e];
+        pe[e] = fast_exp2(__builtin_fmaf(sv, scale_log2, -m_use));
+        // the select is also right when scale_log2 == 0 (-inf * 0 is not a number)
+        if (MASK) pe[e] = (sv == -INFINITY) ? 0.f : pe[e];
+        ls += pe[e];
       }
-      p[kb][0] = __builtin_convertvector(lo, bf16x8);
-      p[kb][1] = __builtin_convertvector(hi, bf16x8);
+      return __builtin_convertvector(pe, bf16x8);
+    };
+    bf16x8 pg[2];
+    pg[0] = probs(0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int g = 0; g < kGroups; ++g) {
+      if (g + 1 < kGroups) pg[(g + 1) & 1] = probs(g + 1);
+#pragma unroll
+      for (int db = 0; db < kDBlocks; ++db)
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[g & 1][db], pg[g & 1], o[db], 0, 0, 0);
+      if (g + 2 < kGroups) read_v_slice(v_lds, g + 2, vop[g & 1]);
+      __builtin_amdgcn_sched_barrier(0);
     }
     l += ls;
-
-    // O^T += V^T P^T.  Slice t of key block kb holds, for this lane's half, keys
-    // kb*32 + 16t + 4*half + {0..3} and the same + 8 (matching the S^T registers).
-#pragma unroll
-    for (int db = 0; db < kDBlocks; ++db) {
-#pragma unroll
-      for (int kb = 0; kb < NKB; ++kb) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const char* vp = v_lds + (kb * 32 + 16 * t) * (D * 2) + v_off[db];
-          const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (s16x4 __attribute__((address_space(3)))*)(vp));
-          const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (s16x4 __attribute__((address_space(3)))*)(vp + 8 * (D * 2)));
-          const s16x8 v8 = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v8),
-                                                          p[kb][t], o[db], 0, 0, 0);
-        }
-      }
-    }
   }
 };
 
@@ -281,38 +315,39 @@ struct Ring {
 };
 
 // Walks tiles [kt_a, kt_b) through the NS-stage ring.  Self-contained: starts
-// with no load in flight and ends with none.
+// with no load in flight and ends with none.  Tile loads run NS-1 tiles ahead.
 template <int D, int NW, int NS, bool MASK>
 __device__ __forceinline__ void run_tiles(RowBlock<D>& rb, const AttnArgs& args, ConstI32Ptr pt,
                                           int kt_a, int kt_b, int kv_total, int kv_head,
                                           const Ring& ring, int wave, int lane) {
   using G = TileGeom<D, NW>;
   constexpr int kStage = PrefillShape<D, NW, NS>::kStageBytes;
+  constexpr int kAhead = NS - 1;  // tiles in flight beyond the current one, plus one
   if (kt_a >= kt_b) return;
   const int half = lane >> 5;
   const int last = kt_b - 1;
   // prologue: tiles kt_a .. kt_a+NS-2 (clamped: a repeated tile is loaded again, harmlessly)
 #pragma unroll
-  for (int s = 0; s < NS - 1; ++s) {
+  for (int s = 0; s < kAhead; ++s) {
     const int tile = min(kt_a + s, last);
     const int page = tile_page<D, NW>(pt, tile, kv_total, wave);
     issue_tile<D, NW>(args, page, tile, kv_total, kv_head, ring.lds_addr + s * kStage,
                       ring.lds_addr + s * kStage + G::kTileBytes, wave, lane);
   }
   // page id of the next tile to issue, fetched one step ahead of its use
-  int page_next = tile_page<D, NW>(pt, min(kt_a + NS - 1, last), kv_total, wave);
+  int page_next = tile_page<D, NW>(pt, min(kt_a + kAhead, last), kv_total, wave);
   for (int kt = kt_a; kt < kt_b; kt += NS) {
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       const int cur = kt + s;
       if (cur < kt_b) {
-        // this wavefront's loads of tile `cur` have landed (the NS-2 younger tiles may fly);
-        // after the barrier everyone's have, and everyone is done with the stage refilled next
-        ring_barrier<(NS - 2) * G::kLoadsPerWaveTile>();
-        const uint32_t nxt = ring.lds_addr + ((s + NS - 1) % NS) * kStage;
-        issue_tile<D, NW>(args, page_next, min(cur + NS - 1, last), kv_total, kv_head, nxt,
+        // this wavefront's loads of tile `cur` have landed (the younger tiles may fly); after
+        // the barrier everyone's have, and everyone is done with the stage refilled next
+        ring_barrier<(kAhead - 1) * G::kLoadsPerWaveTile>();
+        const uint32_t nxt = ring.lds_addr + ((s + kAhead) % NS) * kStage;
+        issue_tile<D, NW>(args, page_next, min(cur + kAhead, last), kv_total, kv_head, nxt,
                           nxt + G::kTileBytes, wave, lane);
-        page_next = tile_page<D, NW>(pt, min(cur + NS, last), kv_total, wave);
+        page_next = tile_page<D, NW>(pt, min(cur + kAhead + 1, last), kv_total, wave);
         const char* st = ring.base + s * kStage;
         rb.template step<2, MASK>(st, st + G::kTileBytes, cur * G::kTileKeys, half);
       }
@@ -321,8 +356,10 @@ __device__ __forceinline__ void run_tiles(RowBlock<D>& rb, const AttnArgs& args,
   ring_barrier<0>();
 }
 
+// (the launch bound is 512 also for the 4-wavefront variant: it makes the compiler budget
+// for two wavefronts per SIMD, at most 256 vector registers, all architectural)
 template <int D, int NW, int NS>
-__global__ void __launch_bounds__(NW * 64) prefill_kernel(const AttnArgs args) {
+__global__ void __launch_bounds__(512) prefill_kernel(const AttnArgs args) {
   using Shape = PrefillShape<D, NW, NS>;
   __shared__ __attribute__((aligned(1024))) char lds[Shape::kLdsBytes];
   const Ring stages{lds, lds_address(lds)};
@@ -379,7 +416,7 @@ __global__ void __launch_bounds__(NW * 64) prefill_kernel(const AttnArgs args) {
   run_tiles<D, NW, NS, false>(rb, args, pt, kt_begin, kt_mid, kv_total, kv_head, stages, wave,
                               lane);
   run_tiles<D, NW, NS, true>(rb, args, pt, kt_mid, kt_end, kv_total, kv_head, stages, wave,
-                              lane);
+                             lane);
 
   const bool direct = sd.n_split == 1;
   float* o_base = direct ? args.out : args.part_o;
