@@ -47,6 +47,15 @@ __device__ __forceinline__ void async_load16(const void* gptr, uint32_t lds_addr
                : "s"(lds_addr_uniform), "v"(gptr)
                : "m0", "memory");
 }
+// Same, with the global address split into a wave-uniform base (scalar registers)
+// and a 32-bit per-lane byte offset: no vector-ALU address arithmetic per load.
+__device__ __forceinline__ void async_load16(const void* base_uniform, uint32_t lane_off,
+                                             uint32_t lds_addr_uniform) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr_uniform), "v"(lane_off), "s"(base_uniform)
+               : "m0", "memory");
+}
 
 // Byte address of a __shared__ object inside the workgroup's LDS allocation.
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
@@ -92,29 +101,58 @@ __device__ __forceinline__ int tile_page(ConstI32Ptr pt, int tile, int kv_total,
   return pt[__builtin_amdgcn_readfirstlane(idx)];
 }
 
-// Issues this wavefront's share of the asynchronous loads of one 64-key tile.
-
+// This wavefront's share of the asynchronous loads of a 64-key tile: which rows
+// (all inside one page) and, per lane, which 16-byte chunk of which row.  The
+// per-lane byte offsets inside the page are the same for every tile that lies
+// wholly inside the sequence, so they are computed once.
 template <int D, int NW>
-__device__ __forceinline__ void issue_tile(const AttnArgs& args, int page, int tile,
-                                           int kv_total, int kv_head, uint32_t k_stage,
-                                           uint32_t v_stage, int wave, int lane) {
+struct TileLoader {
   using G = TileGeom<D, NW>;
-  const int row0 = wave * G::kRowsPerWave;       // wave-uniform
-  const char* kp = reinterpret_cast<const char*>(args.k_pool);
-  const char* vp = reinterpret_cast<const char*>(args.v_pool);
-  const int64_t page_off = ((int64_t)page * args.h_kv + kv_head) * (kPageSize * D * 2);
-  const int r_in = lane / G::kChunksPerRow;
-  const int pos = lane % G::kChunksPerRow;
+  uint32_t k_off[G::kInstrPerWave];  // byte offset inside the (page, KV head) block
+  uint32_t v_off[G::kInstrPerWave];
+  int row0;                          // first row of the tile this wavefront loads (uniform)
+  int r_in, pos;
+
+  __device__ __forceinline__ void init(int wave, int lane) {
+    row0 = wave * G::kRowsPerWave;
+    r_in = lane / G::kChunksPerRow;
+    pos = lane % G::kChunksPerRow;
 #pragma unroll
-  for (int j = 0; j < G::kInstrPerWave; ++j) {
-    const int row = row0 + j * G::kRowsPerInstr + r_in;  // row inside the tile
-    const int t = min(tile * G::kTileKeys + row, kv_total - 1);
-    const int64_t off = page_off + (t & 15) * (D * 2);
-    const int lds_off = (row0 + j * G::kRowsPerInstr) * (D * 2);  // wave-uniform
-    async_load16(kp + off + Swz<D>::k(row, pos) * 16, k_stage + lds_off);
-    async_load16(vp + off + Swz<D>::v(row, pos) * 16, v_stage + lds_off);
+    for (int j = 0; j < G::kInstrPerWave; ++j) {
+      const int row = row0 + j * G::kRowsPerInstr + r_in;
+      k_off[j] = (row & 15) * (D * 2) + Swz<D>::k(row, pos) * 16;
+      v_off[j] = (row & 15) * (D * 2) + Swz<D>::v(row, pos) * 16;
+    }
   }
-}
+
+  // page = id of the page holding rows row0.. of tile `tile` (see tile_page()).
+  __device__ __forceinline__ void issue(const AttnArgs& args, int page, int tile, int kv_total,
+                                        int kv_head, uint32_t k_stage, uint32_t v_stage) const {
+    const int64_t page_off = ((int64_t)page * args.h_kv + kv_head) * (kPageSize * D * 2);
+    const char* kp = reinterpret_cast<const char*>(args.k_pool) + page_off;  // wave-uniform
+    const char* vp = reinterpret_cast<const char*>(args.v_pool) + page_off;
+    if ((tile + 1) * G::kTileKeys <= kv_total) {
+#pragma unroll
+      for (int j = 0; j < G::kInstrPerWave; ++j) {
+        const uint32_t lds_off = (row0 + j * G::kRowsPerInstr) * (D * 2);  // wave-uniform
+        async_load16(kp, k_off[j], k_stage + lds_off);
+        async_load16(vp, v_off[j], v_stage + lds_off);
+      }
+    } else {
+      // last, ragged tile: keys past the end are clamped to the last one (masked, but finite)
+#pragma unroll
+      for (int j = 0; j < G::kInstrPerWave; ++j) {
+        const int row = row0 + j * G::kRowsPerInstr + r_in;
+        const int t = min(tile * G::kTileKeys + row, kv_total - 1);
+        const uint32_t lds_off = (row0 + j * G::kRowsPerInstr) * (D * 2);
+        async_load16(kp, (uint32_t)((t & 15) * (D * 2) + Swz<D>::k(row, pos) * 16),
+                     k_stage + lds_off);
+        async_load16(vp, (uint32_t)((t & 15) * (D * 2) + Swz<D>::v(row, pos) * 16),
+                     v_stage + lds_off);
+      }
+    }
+  }
+};
 
 // Softmax state and accumulators of one wavefront (32 query rows).
 template <int D>
@@ -226,23 +264,30 @@ struct RowBlock {
         }
         mx = fmaxf(mx, s[kb][e]);
       }
-    mx = max_halves(mx);
-    const float m_old = m;
-    const float m_new = fmaxf(m_old, mx * scale_log2);  // scale_log2 >= 0
-    // a row that has seen no key yet keeps m = -inf; exponentiate against 0 then
-    const float m_use = (MASK && m_new == -INFINITY) ? 0.f : m_new;
-    if (__any(m_new != m_old)) {
-      const float alpha = fast_exp2(m_old - m_use);
+    mx = max_halves(mx) * scale_log2;  // scale_log2 >= 0
+    // m is the reference point of the exponentials, not necessarily the true running
+    // maximum: it is moved up (and the accumulators rescaled) only when some row's maximum
+    // exceeds it by more than kRescaleSlack, so that p <= 2^kRescaleSlack.  The common factor
+    // cancels in O = acc / l and LSE = m + log2(l); after the first few tiles of a long
+    // sequence the rescale practically never runs.
+    if (__any(mx > m + kRescaleSlack)) {
+      const float m_new = fmaxf(m, mx);
+      // a row that has seen no key yet keeps m = -inf: nothing to rescale
+      const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m - m_new);
       l *= alpha;
 #pragma unroll
       for (int db = 0; db < kDBlocks; ++db)
 #pragma unroll
         for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
+      m = m_new;
     }
-    m = m_new;
+    // exponentiate against 0 while the row has no key
+    const float m_use = (MASK && m == -INFINITY) ? 0.f : m;
 
     float ls = 0.f;
-    // P^T operand of slice g: elements 8*(g%2) .. +7 of S^T block g/2
+    // P^T operand of slice g: elements 8*(g%2) .. +7 of S^T block g/2.  The row sum is
+    // taken over the fp32 values (a sum of the bf16-rounded ones, two per instruction with
+    // the bf16 dot product, costs up to 4e-3 in LSE on short rows).
     auto probs = [&](int g) -> bf16x8 {
       f32x8 pe;
 #pragma unroll
@@ -319,7 +364,8 @@ struct Ring {
 template <int D, int NW, int NS, bool MASK>
 __device__ __forceinline__ void run_tiles(RowBlock<D>& rb, const AttnArgs& args, ConstI32Ptr pt,
                                           int kt_a, int kt_b, int kv_total, int kv_head,
-                                          const Ring& ring, int wave, int lane) {
+                                          const Ring& ring, const TileLoader<D, NW>& ld,
+                                          int wave, int lane) {
   using G = TileGeom<D, NW>;
   constexpr int kStage = PrefillShape<D, NW, NS>::kStageBytes;
   constexpr int kAhead = NS - 1;  // tiles in flight beyond the current one, plus one
@@ -331,8 +377,8 @@ __device__ __forceinline__ void run_tiles(RowBlock<D>& rb, const AttnArgs& args,
   for (int s = 0; s < kAhead; ++s) {
     const int tile = min(kt_a + s, last);
     const int page = tile_page<D, NW>(pt, tile, kv_total, wave);
-    issue_tile<D, NW>(args, page, tile, kv_total, kv_head, ring.lds_addr + s * kStage,
-                      ring.lds_addr + s * kStage + G::kTileBytes, wave, lane);
+    ld.issue(args, page, tile, kv_total, kv_head, ring.lds_addr + s * kStage,
+             ring.lds_addr + s * kStage + G::kTileBytes);
   }
   // page id of the next tile to issue, fetched one step ahead of its use
   int page_next = tile_page<D, NW>(pt, min(kt_a + kAhead, last), kv_total, wave);
@@ -345,8 +391,8 @@ __device__ __forceinline__ void run_tiles(RowBlock<D>& rb, const AttnArgs& args,
         // the barrier everyone's have, and everyone is done with the stage refilled next
         ring_barrier<(kAhead - 1) * G::kLoadsPerWaveTile>();
         const uint32_t nxt = ring.lds_addr + ((s + kAhead) % NS) * kStage;
-        issue_tile<D, NW>(args, page_next, min(cur + kAhead, last), kv_total, kv_head, nxt,
-                          nxt + G::kTileBytes, wave, lane);
+        ld.issue(args, page_next, min(cur + kAhead, last), kv_total, kv_head, nxt,
+                 nxt + G::kTileBytes);
         page_next = tile_page<D, NW>(pt, min(cur + kAhead + 1, last), kv_total, wave);
         const char* st = ring.base + s * kStage;
         rb.template step<2, MASK>(st, st + G::kTileBytes, cur * G::kTileKeys, half);
@@ -413,10 +459,12 @@ __global__ void __launch_bounds__(512) prefill_kernel(const AttnArgs args) {
   const int kt_mid = max(kt_begin, min(kt_end, unmasked_keys / 64));
 
   ConstI32Ptr pt = (ConstI32Ptr)(args.page_table + sd.pt_off);
-  run_tiles<D, NW, NS, false>(rb, args, pt, kt_begin, kt_mid, kv_total, kv_head, stages, wave,
-                              lane);
-  run_tiles<D, NW, NS, true>(rb, args, pt, kt_mid, kt_end, kv_total, kv_head, stages, wave,
-                             lane);
+  TileLoader<D, NW> loader;
+  loader.init(wave, lane);
+  run_tiles<D, NW, NS, false>(rb, args, pt, kt_begin, kt_mid, kv_total, kv_head, stages, loader,
+                              wave, lane);
+  run_tiles<D, NW, NS, true>(rb, args, pt, kt_mid, kt_end, kv_total, kv_head, stages, loader,
+                             wave, lane);
 
   const bool direct = sd.n_split == 1;
   float* o_base = direct ? args.out : args.part_o;
