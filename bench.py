@@ -177,7 +177,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": kern_tflops / PEAK_BF16_TFLOPS,
                      "traffic": traffic_from_profile("prefill_kernel_cfg2_pmc.txt"),
-                     "kernel": "prefill_kernel<128,8,3>", "event_ms_mean": t["event_ms_mean"],
+                     "kernel": "prefill_kernel<128,8,4>", "event_ms_mean": t["event_ms_mean"],
                      "event_ms_min": t["event_ms_min"]},
     })
     if "cpu" in sections:

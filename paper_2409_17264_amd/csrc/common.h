@@ -9,6 +9,7 @@ namespace medha {
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -20,7 +21,7 @@ constexpr int kPageSize = 16;     // tokens per KV page
 constexpr int kThreads = 256;     // threads per workgroup (4 wavefronts of 64)
 constexpr int kWaves = 4;
 constexpr int kXcds = 8;          // accelerator dies; workgroup i is dispatched to die i % 8
-constexpr int kPrefillStages = 3;  // K/V tiles in flight per workgroup (LDS ring)
+constexpr int kPrefillStages = 4;  // K/V tiles in flight per workgroup (LDS ring)
 constexpr int kMaxInlineSeq = 64; // sequence descriptors that travel as kernel arguments
 constexpr float kRescaleSlack = 8.f;  // log2 units a row maximum may exceed the softmax reference
 constexpr float kLog2e = 1.4426950408889634f;

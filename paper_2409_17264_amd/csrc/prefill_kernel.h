@@ -18,6 +18,9 @@
 // pattern for the 16-byte K reads, another for the 8-byte transposing V reads).
 #pragma once
 
+#include <type_traits>
+#include <utility>
+
 #include "common.h"
 
 namespace medha {
@@ -155,6 +158,16 @@ struct TileLoader {
 };
 
 // Softmax state and accumulators of one wavefront (32 query rows).
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), in order.
+template <int... Is, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F& f) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
 template <int D>
 struct RowBlock {
   static constexpr int kSlices = D / 16;
@@ -169,7 +182,10 @@ struct RowBlock {
   int k_off[kSlices];
   int v_off[kDBlocks];
 
-  __device__ __forceinline__ void init(float scale, int lane) {
+  // v_bias: constant added to the V^T read offsets (the caller subtracts it from the V tile
+  // pointers it passes; with it the pointers' constant parts fit the LDS instructions'
+  // 16-bit immediate offset and cost no address arithmetic).
+  __device__ __forceinline__ void init(float scale, int lane, int v_bias = 0) {
     scale_log2 = scale;
     m = -INFINITY;
     l = 0.f;
@@ -186,7 +202,8 @@ struct RowBlock {
 #pragma unroll
     for (int db = 0; db < kDBlocks; ++db) {
       const int chunk = 4 * db + 2 * dhalf + ((l16 & 3) >> 1);
-      v_off[db] = vrow * (D * 2) + Swz<D>::v(vrow, chunk) * 16 + (l16 & 1) * 8;
+      v_off[db] = vrow * (D * 2) + Swz<D>::v(vrow, chunk) * 16 + (l16 & 1) * 8 + v_bias;
+      asm volatile("" : "+v"(v_off[db]));  // opaque: stays one register, constants stay immediates
     }
   }
 
@@ -207,69 +224,54 @@ struct RowBlock {
     }
   }
 
-  // One tile of NKB blocks of 32 keys (2*NKB slices of 16 keys).  The instruction
-  // order is laid out by hand as a software pipeline, and fenced so that it
-  // stays that way: LDS operand reads are issued two steps before the MFMAs that
-  // consume them (their latency would otherwise stall every MFMA), and the
-  // exponentials of slice g+1 sit between the MFMAs of slice g.
-  //   S^T = K Q^T:    A = 32 keys x 16 dims from LDS, B = Q^T from registers.
-  //   softmax:        mask on diagonal tiles, row maximum (lane-local + one
-  //                   half-wave exchange), accumulator rescale only if some
-  //                   row's maximum moved, p = exp2(s*scale_log2 - m), row sum.
-  //   O^T += V^T P^T: B = P^T slice taken from the S^T registers of the same
-  //                   keys (bf16, round to nearest even), A = V^T slice.
-  // key0 = sequence index of the tile's first key.
-  template <int NKB, bool MASK>
-  __device__ __forceinline__ void step(const char* k_lds, const char* v_lds, int key0, int half) {
-    constexpr int kGroups = 2 * NKB;
-    bf16x8 vop[2][kDBlocks];
-    read_v_slice(v_lds, 0, vop[0]);
-    read_v_slice(v_lds, 1, vop[1]);
-
-    f32x16 s[NKB];
-    {
-      bf16x8 a[3][NKB];
+  // A tile of NKB blocks of 32 keys (2*NKB slices of 16 keys) is two phases:
+  //   qk():         S^T = K Q^T.  A = 32 keys x 16 dims from LDS, B = Q^T from registers.
+  //   softmax_pv(): mask on diagonal tiles, row maximum (lane-local + one half-wave
+  //                 exchange), p = exp2(s*scale_log2 - m), row sum, then
+  //                 O^T += V^T P^T with B = P^T slice taken from the S^T registers
+  //                 of the same keys (bf16, round to nearest even), A = V^T slice.
+  // The instruction order of both is laid out by hand as a software pipeline and
+  // fenced so that it stays that way: LDS operand reads are issued a few steps
+  // before the MFMAs that consume them (their latency would otherwise stall every
+  // MFMA), and exponentials sit between MFMAs.  fused() below interleaves the
+  // qk() of the next tile with the softmax_pv() of the current one.
+  template <int NKB>
+  __device__ __forceinline__ void qk(const char* k_lds, f32x16 (&s)[NKB]) const {
+    bf16x8 a[3][NKB];
 #pragma unroll
-      for (int kb = 0; kb < NKB; ++kb) {
+    for (int kb = 0; kb < NKB; ++kb) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
-        // rows kb*32 + col: the swizzle only looks at row bits below 32
-        a[0][kb] = *reinterpret_cast<const bf16x8*>(k_lds + kb * 32 * (D * 2) + k_off[0]);
-        a[1][kb] = *reinterpret_cast<const bf16x8*>(k_lds + kb * 32 * (D * 2) + k_off[1]);
-      }
-      __builtin_amdgcn_sched_barrier(0);
+      for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
+      // rows kb*32 + col: the swizzle only looks at row bits below 32
+      a[0][kb] = *reinterpret_cast<const bf16x8*>(k_lds + kb * 32 * (D * 2) + k_off[0]);
+      a[1][kb] = *reinterpret_cast<const bf16x8*>(k_lds + kb * 32 * (D * 2) + k_off[1]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int sl = 0; sl < kSlices; ++sl) {
-        if (sl + 2 < kSlices) {
-#pragma unroll
-          for (int kb = 0; kb < NKB; ++kb)
-            a[(sl + 2) % 3][kb] =
-                *reinterpret_cast<const bf16x8*>(k_lds + kb * 32 * (D * 2) + k_off[sl + 2]);
-        }
+    for (int sl = 0; sl < kSlices; ++sl) {
+      if (sl + 2 < kSlices) {
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb)
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[sl % 3][kb], q[sl], s[kb], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+          a[(sl + 2) % 3][kb] =
+              *reinterpret_cast<const bf16x8*>(k_lds + kb * 32 * (D * 2) + k_off[sl + 2]);
       }
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb)
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[sl % 3][kb], q[sl], s[kb], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
+  }
 
-    float mx = -INFINITY;
-#pragma unroll
-    for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        if (MASK) {
-          const int t = key0 + kb * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-          s[kb][e] = (t <= limit) ? s[kb][e] : -INFINITY;
-        }
-        mx = fmaxf(mx, s[kb][e]);
-      }
-    mx = max_halves(mx) * scale_log2;  // scale_log2 >= 0
-    // m is the reference point of the exponentials, not necessarily the true running
-    // maximum: it is moved up (and the accumulators rescaled) only when some row's maximum
-    // exceeds it by more than kRescaleSlack, so that p <= 2^kRescaleSlack.  The common factor
-    // cancels in O = acc / l and LSE = m + log2(l); after the first few tiles of a long
-    // sequence the rescale practically never runs.
+  // Row maximum of the (masked) scores against the running reference point m.
+  // m is the reference point of the exponentials, not necessarily the true running
+  // maximum: it is moved up (and the accumulators rescaled) only when some row's
+  // maximum exceeds it by more than kRescaleSlack, so that p <= 2^kRescaleSlack.  The
+  // common factor cancels in O = acc / l and LSE = m + log2(l); after the first few
+  // tiles of a long sequence the rescale practically never runs.  Returns the value
+  // to exponentiate against (0 while the row has seen no key).
+  template <bool MASK>
+  __device__ __forceinline__ float update_reference(float mx_raw) {
+    const float mx = max_halves(mx_raw) * scale_log2;  // scale_log2 >= 0
     if (__any(mx > m + kRescaleSlack)) {
       const float m_new = fmaxf(m, mx);
       // a row that has seen no key yet keeps m = -inf: nothing to rescale
@@ -281,8 +283,35 @@ struct RowBlock {
         for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
       m = m_new;
     }
-    // exponentiate against 0 while the row has no key
-    const float m_use = (MASK && m == -INFINITY) ? 0.f : m;
+    return (MASK && m == -INFINITY) ? 0.f : m;
+  }
+
+  // One probability: exp2(s*scale_log2 - m_use), 0 for a masked score (the select is
+  // also right when scale_log2 == 0, where -inf * 0 is not a number).
+  template <bool MASK>
+  __device__ __forceinline__ float prob(float sv, float m_use) const {
+    const float p = fast_exp2(__builtin_fmaf(sv, scale_log2, -m_use));
+    return (MASK && sv == -INFINITY) ? 0.f : p;
+  }
+
+  // vop holds the V^T operands of slices 0 and 1, already requested by the caller.
+  // key0 = sequence index of the tile's first key.
+  template <int NKB, bool MASK>
+  __device__ __forceinline__ void softmax_pv(f32x16 (&s)[NKB], const char* v_lds,
+                                             bf16x8 (&vop)[2][kDBlocks], int key0, int half) {
+    constexpr int kGroups = 2 * NKB;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        if (MASK) {
+          const int t = key0 + kb * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+          s[kb][e] = (t <= limit) ? s[kb][e] : -INFINITY;
+        }
+        mx = fmaxf(mx, s[kb][e]);
+      }
+    const float m_use = update_reference<MASK>(mx);
 
     float ls = 0.f;
     // P^T operand of slice g: elements 8*(g%2) .. +7 of S^T block g/2.  The row sum is
@@ -292,10 +321,7 @@ struct RowBlock {
       f32x8 pe;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const float sv = s[g >> 1][8 * (g & 1) + e];
-        pe[e] = fast_exp2(__builtin_fmaf(sv, scale_log2, -m_use));
-        // the select is also right when scale_log2 == 0 (-inf * 0 is not a number)
-        if (MASK) pe[e] = (sv == -INFINITY) ? 0.f : pe[e];
+        pe[e] = prob<MASK>(s[g >> 1][8 * (g & 1) + e], m_use);
         ls += pe[e];
       }
       return __builtin_convertvector(pe, bf16x8);
@@ -312,6 +338,155 @@ struct RowBlock {
       if (g + 2 < kGroups) read_v_slice(v_lds, g + 2, vop[g & 1]);
       __builtin_amdgcn_sched_barrier(0);
     }
+    l += ls;
+  }
+
+  // One whole tile: the first V^T operands are requested ahead of phase 1.
+  template <int NKB, bool MASK>
+  __device__ __forceinline__ void step(const char* k_lds, const char* v_lds, int key0, int half) {
+    bf16x8 vop[2][kDBlocks];
+    read_v_slice(v_lds, 0, vop[0]);
+    read_v_slice(v_lds, 1, vop[1]);
+    f32x16 s[NKB];
+    qk<NKB>(k_lds, s);
+    softmax_pv<NKB, MASK>(s, v_lds, vop, key0, half);
+  }
+
+  // Steady state of the 64-key tile walk: softmax_pv() of the current tile (scores
+  // sc, V tile v_cur, first key key0) and qk() of the next tile (K tile k_next, scores
+  // into sn) as ONE stream of kSlots slots.  Slot i holds one MFMA -- first the
+  // next tile's S^T = K Q^T, then the current tile's O^T += V^T P^T, slice by slice --
+  // the LDS read of the operand of slot i+3, and a share of the current tile's softmax
+  // arithmetic, spread so that every slice's P^T is complete before its MFMAs.  The
+  // vector ALU is the scarce unit here (an exponential costs two issue slots, and the
+  // matrix instructions go through the same issue port), so the count of its
+  // instructions per tile decides the speed.
+  //
+  // Tiles that every row sees in full (MASK false) are therefore exponentiated
+  // SPECULATIVELY against the reference point m as it stands, without looking for the
+  // row maximum first: once m has been set from a row's first tile, a later score
+  // exceeds it by more than a few units only in contrived inputs.  The speculation is
+  // checked on the row sums, twice per tile and before any MFMA consumes the
+  // probabilities in question (all p >= 0, so a sum within kSpecLimit bounds each
+  // term, and an overflow to +inf shows as well); a failed check takes the exact
+  // route for those two slices: maximum, move of the reference point, rescale, new
+  // probabilities.  Diagonal tiles (MASK true) always take the exact route.
+  static constexpr float kSpecLimit = 1073741824.f;  // 2^30
+
+  // Exact recomputation of slices 2*KB and 2*KB+1 (score block KB) after a failed check.
+  template <int KB>
+  __device__ __forceinline__ void respeculate(const f32x16 (&sc)[2], uint32_t (&pw)[4][4], float& ls) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[KB][e]);
+    const float m_use = update_reference<false>(mx);
+    ls = 0.f;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      f32x8 pe;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        pe[e] = prob<false>(sc[KB][8 * h + e], m_use);
+        ls += pe[e];
+      }
+      const uint4 w = __builtin_bit_cast(uint4, __builtin_convertvector(pe, bf16x8));
+      pw[2 * KB + h][0] = w.x; pw[2 * KB + h][1] = w.y;
+      pw[2 * KB + h][2] = w.z; pw[2 * KB + h][3] = w.w;
+    }
+  }
+
+  template <bool MASK>
+  __device__ __forceinline__ void fused(const char* k_next, const char* v_cur, f32x16 (&sc)[2],
+                                        f32x16 (&sn)[2], int key0, int half) {
+    constexpr bool kSpec = !MASK;
+    constexpr int kQk = 2 * kSlices;       // MFMAs of the next tile's S^T
+    constexpr int kPv = 4 * kDBlocks;      // MFMAs of the current tile's O^T
+    constexpr int kSlots = kQk + kPv;
+    constexpr int kMaxSlots = kSpec ? 0 : kSlots / 8;  // slots that share the row maximum
+    constexpr int kSpan = 3 * kSlots / 16; // slots over which a slice's exponentials spread
+    // slice g: exponentials in slots [kMaxSlots + g*kSpan, +kSpan), MFMAs from kQk + g*kDBlocks
+    static_assert(kMaxSlots + 4 * kSpan <= kQk + 3 * kDBlocks, "P^T ready before its MFMAs");
+    // the speculation checks close slots 2*kSpan-1 and 4*kSpan-1
+    static_assert(2 * kSpan <= kQk && 4 * kSpan <= kQk + 2 * kDBlocks, "checked before consumed");
+    bf16x8 ka[4], va[4];
+    uint32_t pw[4][4];  // P^T operands of the 4 slices as packed bf16 pairs
+    float mx = -INFINITY, m_use = m, ls = 0.f;
+    float pe_prev = 0.f;
+
+    auto read_operand = [&](int i) {
+      if (i < kQk) {
+        ka[i & 3] = *reinterpret_cast<const bf16x8*>(k_next + (i & 1) * 32 * (D * 2) + k_off[i >> 1]);
+      } else if (i < kSlots) {
+        const int j = i - kQk, g = j / kDBlocks, db = j % kDBlocks;
+        const char* vp = v_cur + g * 16 * (D * 2) + v_off[db];
+        const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (s16x4 __attribute__((address_space(3)))*)(vp));
+        const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (s16x4 __attribute__((address_space(3)))*)(vp + 8 * (D * 2)));
+        va[i & 3] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
+      }
+    };
+    read_operand(0);
+    read_operand(1);
+    read_operand(2);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sn[kb][e] = 0.f;
+    __builtin_amdgcn_sched_barrier(0);
+
+    auto slot = [&](auto slot_index) {
+      constexpr int i = decltype(slot_index)::value;
+      read_operand(i + 3);
+      if constexpr (i < kQk) {
+        sn[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i & 3], q[i >> 1], sn[i & 1], 0, 0, 0);
+      } else {
+        constexpr int j = i - kQk, g = j / kDBlocks, db = j % kDBlocks;
+        const uint4 w = make_uint4(pw[g][0], pw[g][1], pw[g][2], pw[g][3]);
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i & 3], __builtin_bit_cast(bf16x8, w),
+                                                        o[db], 0, 0, 0);
+      }
+      // this slot's share of the softmax of the current tile
+      if constexpr (!kSpec && i < kMaxSlots) {
+        constexpr int per = 32 / (kSpec ? 1 : kMaxSlots);
+#pragma unroll
+        for (int f = i * per; f < (i + 1) * per; ++f) {
+          if (MASK) {
+            const int t = key0 + (f >> 4) * 32 + 8 * ((f & 15) >> 2) + 4 * half + (f & 3);
+            sc[f >> 4][f & 15] = (t <= limit) ? sc[f >> 4][f & 15] : -INFINITY;
+          }
+          mx = fmaxf(mx, sc[f >> 4][f & 15]);
+        }
+      }
+      if constexpr (!kSpec && i == kMaxSlots) m_use = update_reference<MASK>(mx);
+      if constexpr (i >= kMaxSlots && i < kMaxSlots + 4 * kSpan) {
+        constexpr int g = (i - kMaxSlots) / kSpan, r = (i - kMaxSlots) % kSpan;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if ((e * kSpan) / 8 == r) {
+            const float pe = prob<MASK>(sc[g >> 1][8 * (g & 1) + e], m_use);
+            ls += pe;
+            if (e & 1) {
+              const f32x2 pair = {pe_prev, pe};
+              pw[g][e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pair, bf16x2));
+            } else {
+              pe_prev = pe;
+            }
+          }
+      }
+      asm volatile("" : "+v"(ls));  // keeps the additions in their slots
+      if constexpr (kSpec && (i == 2 * kSpan - 1 || i == 4 * kSpan - 1)) {
+        // ls covers the two slices just finished
+        if (__builtin_expect(__any(!(ls <= kSpecLimit)), 0)) {
+          respeculate<(i == 2 * kSpan - 1) ? 0 : 1>(sc, pw, ls);
+          m_use = m;
+        }
+        l += ls;
+        ls = 0.f;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    static_for<kSlots>(slot);
     l += ls;
   }
 };
@@ -359,45 +534,74 @@ struct Ring {
   uint32_t lds_addr;  // the same place as an LDS byte address, for the tile loads
 };
 
-// Walks tiles [kt_a, kt_b) through the NS-stage ring.  Self-contained: starts
-// with no load in flight and ends with none.  Tile loads run NS-1 tiles ahead.
+// Walks tiles [kt_a, kt_b) through the 4-stage ring.  Self-contained: starts with
+// no load in flight and ends with none.
+//
+// Iteration `cur` runs RowBlock::fused(): the softmax and P*V of tile cur together
+// with the Q*K^T of tile cur+1, whose scores it hands to the next iteration in
+// registers (two score sets, used alternately).  So at the barrier that opens
+// iteration cur, tile cur+1 must have landed, tile cur+2 is in flight, and tile cur+3
+// is issued into the stage of tile cur-1, which everybody left at that barrier.
 template <int D, int NW, int NS, bool MASK>
 __device__ __forceinline__ void run_tiles(RowBlock<D>& rb, const AttnArgs& args, ConstI32Ptr pt,
                                           int kt_a, int kt_b, int kv_total, int kv_head,
                                           const Ring& ring, const TileLoader<D, NW>& ld,
                                           int wave, int lane) {
   using G = TileGeom<D, NW>;
-  constexpr int kStage = PrefillShape<D, NW, NS>::kStageBytes;
-  constexpr int kAhead = NS - 1;  // tiles in flight beyond the current one, plus one
+  static_assert(NS == 4, "stages: tile cur, cur+1, cur+2 (in flight), cur+3 (being issued)");
+  constexpr int kTile = G::kTileBytes;  // K tiles fill the low half of the ring, V tiles the high
   if (kt_a >= kt_b) return;
   const int half = lane >> 5;
   const int last = kt_b - 1;
-  // prologue: tiles kt_a .. kt_a+NS-2 (clamped: a repeated tile is loaded again, harmlessly)
+  // prologue: tiles kt_a .. kt_a+2 (clamped: a repeated tile is loaded again, harmlessly)
 #pragma unroll
-  for (int s = 0; s < kAhead; ++s) {
+  for (int s = 0; s < 3; ++s) {
     const int tile = min(kt_a + s, last);
     const int page = tile_page<D, NW>(pt, tile, kv_total, wave);
-    ld.issue(args, page, tile, kv_total, kv_head, ring.lds_addr + s * kStage,
-             ring.lds_addr + s * kStage + G::kTileBytes);
+    ld.issue(args, page, tile, kv_total, kv_head, ring.lds_addr + s * kTile,
+             ring.lds_addr + (NS + s) * kTile);
   }
   // page id of the next tile to issue, fetched one step ahead of its use
-  int page_next = tile_page<D, NW>(pt, min(kt_a + kAhead, last), kv_total, wave);
-  for (int kt = kt_a; kt < kt_b; kt += NS) {
+  int page_next = tile_page<D, NW>(pt, min(kt_a + 3, last), kv_total, wave);
+  f32x16 s0[2], s1[2];  // scores of the even / odd tiles (counted from kt_a)
+  ring_barrier<2 * G::kLoadsPerWaveTile>();  // tile kt_a has landed, for everyone
+  rb.template qk<2>(ring.base, s0);
+  if (!MASK) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int f = 0; f < 32; ++f) mx = fmaxf(mx, s0[f >> 4][f & 15]);
+    rb.template update_reference<false>(mx);
+  }
+  for (int kt = kt_a; kt < last; kt += NS) {
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       const int cur = kt + s;
-      if (cur < kt_b) {
-        // this wavefront's loads of tile `cur` have landed (the younger tiles may fly); after
-        // the barrier everyone's have, and everyone is done with the stage refilled next
-        ring_barrier<(kAhead - 1) * G::kLoadsPerWaveTile>();
-        const uint32_t nxt = ring.lds_addr + ((s + kAhead) % NS) * kStage;
-        ld.issue(args, page_next, min(cur + kAhead, last), kv_total, kv_head, nxt,
-                 nxt + G::kTileBytes);
-        page_next = tile_page<D, NW>(pt, min(cur + kAhead + 1, last), kv_total, wave);
-        const char* st = ring.base + s * kStage;
-        rb.template step<2, MASK>(st, st + G::kTileBytes, cur * G::kTileKeys, half);
+      if (cur < last) {
+        // this wavefront's loads of tile cur+1 have landed (tile cur+2 may fly); after the
+        // barrier everyone's have, and everyone is done with the stage refilled next
+        ring_barrier<G::kLoadsPerWaveTile>();
+        const uint32_t nxt = ring.lds_addr + ((s + 3) % NS) * kTile;
+        ld.issue(args, page_next, min(cur + 3, last), kv_total, kv_head, nxt, nxt + NS * kTile);
+        page_next = tile_page<D, NW>(pt, min(cur + 4, last), kv_total, wave);
+        const char* k_next = ring.base + ((s + 1) % NS) * kTile;
+        const char* v_cur = ring.base + s * kTile;  // + the bias in rb.v_off
+        if (s & 1)
+          rb.template fused<MASK>(k_next, v_cur, s1, s0, cur * G::kTileKeys, half);
+        else
+          rb.template fused<MASK>(k_next, v_cur, s0, s1, cur * G::kTileKeys, half);
       }
     }
+  }
+  // the last tile: its scores are in registers, its V tile landed with its K tile
+  {
+    const char* v_last = ring.base + ((last - kt_a) % NS) * kTile;  // + the bias in rb.v_off
+    bf16x8 vop[2][RowBlock<D>::kDBlocks];
+    rb.read_v_slice(v_last, 0, vop[0]);
+    rb.read_v_slice(v_last, 1, vop[1]);
+    if ((last - kt_a) & 1)
+      rb.template softmax_pv<2, MASK>(s1, v_last, vop, last * G::kTileKeys, half);
+    else
+      rb.template softmax_pv<2, MASK>(s0, v_last, vop, last * G::kTileKeys, half);
   }
   ring_barrier<0>();
 }
@@ -425,7 +629,8 @@ __global__ void __launch_bounds__(512) prefill_kernel(const AttnArgs args) {
   const int col = lane & 31, half = lane >> 5;
 
   RowBlock<D> rb;
-  rb.init(fabsf(args.scale_log2), lane);
+  // V tiles sit NS K-tiles above the ring's base
+  rb.init(fabsf(args.scale_log2), lane, NS * TileGeom<D, NW>::kTileBytes);
 
   const int wg_row0 = row_tile * Shape::kRowsPerWg;
   const int r = wg_row0 + wave * 32 + col;
