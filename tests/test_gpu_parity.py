@@ -146,6 +146,44 @@ def test_needle_is_bit_exact_on_gpu():
                         assert abs(lse[j, h] - np.log(P + j + 1)) < 1e-3
 
 
+# ------------------------------------- scores that outgrow the softmax reference point
+def _rising_keys(profile, n_keys, rng):
+    """Per-key score level g(t); the key vector is g(t) plus small noise in every dim."""
+    t = np.arange(n_keys)
+    if profile == "staircase":       # near the end, every 16-key slice far above the one before
+        return 2.5 * np.maximum(0, t // 16 - (n_keys // 16 - 20))
+    if profile == "jumps":           # flat stretches, rare large jumps at arbitrary keys
+        return np.cumsum(np.where(rng.random(n_keys) < 1 / 200, 4.0, 0.0)) + 0.1 * rng.standard_normal(n_keys)
+    if profile == "ramp":            # slow drift: many tiles pass before the reference must move
+        return 0.003 * t
+    if profile == "sawtooth":        # up and far down again
+        return 3.0 * ((t // 40) % 5)
+    raise ValueError(profile)
+
+
+@pytest.mark.parametrize("d,h_q,h_kv", [(128, 8, 2), (64, 4, 1)])
+@pytest.mark.parametrize("profile", ["staircase", "jumps", "ramp", "sawtooth"])
+def test_scores_rising_along_the_sequence(profile, d, h_q, h_kv):
+    """The prefill kernel exponentiates fully visible tiles against the reference point it
+    already holds and falls back to the exact route when a checked row sum says the
+    scores outgrew it; these inputs make that happen in every position of a tile."""
+    P, chunk = 2000, 130
+    rng = np.random.default_rng(len(profile) * 100 + d)
+    b = wl.make_prefill_batch("rise", h_q, h_kv, d, [P], [chunk], seed=d + len(profile),
+                              poison_unused=True)
+    g = _rising_keys(profile, P + chunk, rng)
+    b.q.fill_(1.0)
+    b.q[:, ::2, :] *= 0.5   # every other head at half the slope
+    for t in range(P + chunk):
+        page, slot = int(b.page_table[t // 16]), t % 16
+        noise = 0.25 * rng.standard_normal((h_kv, d))
+        b.k_pool[page, :, slot, :] = torch.from_numpy(g[t] + noise).to(torch.bfloat16)
+    b = to_dev(b)
+    out, lse = gpu_prefill(b)
+    ro, rl = oracle_prefill(b)
+    check(out, lse, ro, rl, f"rising {profile} d{d}")
+
+
 def test_page_permutation_is_bitwise_invariant_on_gpu():
     a = wl.make_prefill_batch("a", 8, 2, 128, [1000, 300], [200, 1], seed=5)
     num_pages = a.num_pages + 11
