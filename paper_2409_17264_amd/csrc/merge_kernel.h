@@ -9,25 +9,46 @@ namespace medha {
 
 // One thread owns 4 consecutive head-dim elements of one (row, head).  Partial
 // s of that row sits at row index  base + s * stride  of the partial arrays.
+// The partials are taken kBatch at a time with all loads of a batch in flight
+// together (the merge is a chain of memory latencies, nothing else), and batches
+// are folded with the same online rescaling the attention kernels use.
 __device__ __forceinline__ void merge_one(const float* __restrict__ part_o,
                                           const float* __restrict__ part_lse, int n_split,
                                           int64_t base, int64_t stride, int h_q, int head, int d,
                                           int d4, float* __restrict__ out_row,
                                           float* __restrict__ lse_out) {
-  float big = -INFINITY;
-  for (int s = 0; s < n_split; ++s)
-    big = fmaxf(big, part_lse[(base + s * stride) * h_q + head]);
+  constexpr int kBatch = 8;
+  float big = -INFINITY, wsum = 0.f;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  float wsum = 0.f;
-  if (big != -INFINITY) {
-    for (int s = 0; s < n_split; ++s) {
-      const int64_t r = (base + s * stride) * h_q + head;
-      const float w = fast_exp2((part_lse[r] - big) * kLog2e);
-      if (w > 0.f) {
+  for (int s0 = 0; s0 < n_split; s0 += kBatch) {
+    float ls[kBatch];
+    f32x4 ov[kBatch];
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      // past the end: the last partial again, with weight 0
+      const int64_t r = (base + min(s0 + i, n_split - 1) * stride) * h_q + head;
+      ls[i] = part_lse[r];
+      ov[i] = *reinterpret_cast<const f32x4*>(part_o + r * d + d4 * 4);
+    }
+    float top = big;
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      if (s0 + i >= n_split) ls[i] = -INFINITY;
+      top = fmaxf(top, ls[i]);
+    }
+    if (top == -INFINITY) continue;  // nothing but empty shards so far
+    const float keep = fast_exp2((big - top) * kLog2e);  // 0 while big is -inf
+    wsum *= keep;
+    acc *= keep;
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      const float w = fast_exp2((ls[i] - top) * kLog2e);
+      if (w > 0.f) {  // an empty shard's O is never read into the sum
         wsum += w;
-        acc += *reinterpret_cast<const f32x4*>(part_o + r * d + d4 * 4) * w;
+        acc += ov[i] * w;
       }
     }
+    big = top;
   }
   const float inv = wsum > 0.f ? 1.f / wsum : 0.f;
   *reinterpret_cast<f32x4*>(out_row + d4 * 4) = acc * inv;

@@ -395,7 +395,10 @@ struct RowBlock {
     }
   }
 
-  template <bool MASK>
+  //
+  // QK false leaves the next tile out (the walk's last tile): the same slots without
+  // their K reads and S^T MFMAs; k_next and sn are not touched.
+  template <bool MASK, bool QK = true>
   __device__ __forceinline__ void fused(const char* k_next, const char* v_cur, f32x16 (&sc)[2],
                                         f32x16 (&sn)[2], int key0, int half) {
     constexpr bool kSpec = !MASK;
@@ -415,7 +418,8 @@ struct RowBlock {
 
     auto read_operand = [&](int i) {
       if (i < kQk) {
-        ka[i & 3] = *reinterpret_cast<const bf16x8*>(k_next + (i & 1) * 32 * (D * 2) + k_off[i >> 1]);
+        if (QK)
+          ka[i & 3] = *reinterpret_cast<const bf16x8*>(k_next + (i & 1) * 32 * (D * 2) + k_off[i >> 1]);
       } else if (i < kSlots) {
         const int j = i - kQk, g = j / kDBlocks, db = j % kDBlocks;
         const char* vp = v_cur + g * 16 * (D * 2) + v_off[db];
@@ -429,17 +433,20 @@ struct RowBlock {
     read_operand(0);
     read_operand(1);
     read_operand(2);
+    if (QK) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) sn[kb][e] = 0.f;
+        for (int e = 0; e < 16; ++e) sn[kb][e] = 0.f;
+    }
     __builtin_amdgcn_sched_barrier(0);
 
     auto slot = [&](auto slot_index) {
       constexpr int i = decltype(slot_index)::value;
       read_operand(i + 3);
       if constexpr (i < kQk) {
-        sn[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i & 3], q[i >> 1], sn[i & 1], 0, 0, 0);
+        if constexpr (QK)
+          sn[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i & 3], q[i >> 1], sn[i & 1], 0, 0, 0);
       } else {
         constexpr int j = i - kQk, g = j / kDBlocks, db = j % kDBlocks;
         const uint4 w = make_uint4(pw[g][0], pw[g][1], pw[g][2], pw[g][3]);
@@ -595,13 +602,10 @@ __device__ __forceinline__ void run_tiles(RowBlock<D>& rb, const AttnArgs& args,
   // the last tile: its scores are in registers, its V tile landed with its K tile
   {
     const char* v_last = ring.base + ((last - kt_a) % NS) * kTile;  // + the bias in rb.v_off
-    bf16x8 vop[2][RowBlock<D>::kDBlocks];
-    rb.read_v_slice(v_last, 0, vop[0]);
-    rb.read_v_slice(v_last, 1, vop[1]);
     if ((last - kt_a) & 1)
-      rb.template softmax_pv<2, MASK>(s1, v_last, vop, last * G::kTileKeys, half);
+      rb.template fused<MASK, false>(nullptr, v_last, s1, s0, last * G::kTileKeys, half);
     else
-      rb.template softmax_pv<2, MASK>(s0, v_last, vop, last * G::kTileKeys, half);
+      rb.template fused<MASK, false>(nullptr, v_last, s0, s1, last * G::kTileKeys, half);
   }
   ring_barrier<0>();
 }
