@@ -15,11 +15,14 @@ The same JSON line also carries, each measured in its own timed loop:
            at chunk sizes 512..8192: TFLOP/s per chunk size;
   mixed    one 1024-token prefill chunk at a 524,288-token prefix plus 64
            decodes in one call.
+  ceilings what the same device sustains, in the same run, on an MFMA-only loop
+           (N(0,1) bf16 operands) and on a 4 GiB streaming read: context for
+           the data-sheet peaks the roofline fractions use;
 and `cpu_baseline`: the fp64 CPU oracle timed on a bounded sample of rows of
 the headline workload on this machine's host cores (a reported baseline only).
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W]
-                [--sections main,decode,sweep,mixed,cpu[,copy]]
+                [--sections ceilings,main,decode,sweep,mixed,cpu[,copy]]
 """
 import argparse
 import json
@@ -130,7 +133,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--sections", default="main,decode,sweep,mixed,cpu")
+    ap.add_argument("--sections", default="ceilings,main,decode,sweep,mixed,cpu")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (KV-cache parallelism is exercised "
@@ -157,6 +160,34 @@ def main():
             f"{2 * src.numel() / (t['event_ms_mean'] * 1e-3) / 1e9:.0f} GB/s read+write")
         del src, dst
         torch.cuda.empty_cache()
+    # ------------------------------------------------------------ yardsticks
+    ceilings = None
+    if "ceilings" in sections:
+        # what this device sustains on nothing but bf16 MFMAs (N(0,1) operands: switching
+        # power, and with it the clock, depends on the data) and on nothing but reads
+        g = torch.Generator(device="cpu").manual_seed(99)
+        ops = torch.randn(5 * 64 * 8, generator=g).to(torch.bfloat16).cuda()
+        blocks = props.multi_processor_count
+        sink = torch.empty(blocks * 512, dtype=torch.float32, device="cuda")
+        iters = 12000
+        fl = [0.0]
+
+        def run_mfma():
+            fl[0] = medha.ceiling_mfma_bf16(ops, blocks, iters, sink)
+        t = time_calls(run_mfma, 10, 3)
+        mfma_tf = fl[0] / (t["event_ms_mean"] * 1e-3) / 1e12
+        src = torch.empty(1 << 32, dtype=torch.uint8, device="cuda").fill_(3)
+        rblocks = blocks * 8
+        rsink = torch.empty(rblocks * 256 * 16, dtype=torch.uint8, device="cuda")
+        t2 = time_calls(lambda: medha.ceiling_stream_read(src, rblocks, rsink), 10, 3)
+        read_gbps = src.numel() / (t2["event_ms_mean"] * 1e-3) / 1e9
+        log(f"ceilings: MFMA-only bf16 (N(0,1) operands) {mfma_tf:.0f} TFLOP/s "
+            f"({t['event_ms_mean']:.3f} ms); streaming read {read_gbps:.0f} GB/s")
+        ceilings = {"mfma_bf16_tflops": mfma_tf, "stream_read_gbps": read_gbps,
+                    "note": "same device, same run: an MFMA-only loop with N(0,1) bf16 operands "
+                            "and a 4 GiB streaming read; context for the data-sheet peaks"}
+        del src, rsink, sink, ops
+        torch.cuda.empty_cache()
     # ------------------------------------------------------------- headline
     b = wl.config2_llama8b("cuda:0")
     run, out, lse = prefill_runner(b)
@@ -180,6 +211,9 @@ def main():
                      "kernel": "prefill_kernel<128,8,4>", "event_ms_mean": t["event_ms_mean"],
                      "event_ms_min": t["event_ms_min"]},
     })
+    if ceilings is not None:
+        result["ceilings"] = ceilings
+        result["roofline"]["frac_of_measured_ceiling"] = kern_tflops / ceilings["mfma_bf16_tflops"]
     if "cpu" in sections:
         result["cpu_baseline"] = cpu_baseline(b)
         log(f"cpu oracle: {result['cpu_baseline']}")
@@ -216,6 +250,9 @@ def main():
                          "frac": gbps / PEAK_HBM_GBPS,
                          "traffic": traffic_from_profile("decode_kernel_cfg3_pmc.txt"),
                          "kernel": "decode_kernel<128> (+ split_merge_kernel, lse_merge_kernel)"}}
+        if ceilings is not None:
+            result["decode"]["roofline"]["frac_of_measured_ceiling"] = \
+                gbps / ceilings["stream_read_gbps"]
         del c, pt, po, pl, ws
         torch.cuda.empty_cache()
 
@@ -242,17 +279,40 @@ def main():
     # ---------------------------------------------------------------- mixed
     if "mixed" in sections:
         m = wl.config5_mixed("cuda:0")
+        n_mixed = max(3, args.steps // 3)
         run, _, _ = prefill_runner(m)
-        t = time_calls(run, max(3, args.steps // 3), 2)
+        t = time_calls(run, n_mixed, 2)
         pf = 4.0 * m.d * m.h_q * (1024.0 * 524288 + 1024 * 1025 / 2)
         dec_bytes = 4.0 * m.d * m.h_kv * float(m.meta["decode_lens"].sum())
-        log(f"mixed: {t['event_ms_mean']:.3f} ms")
+        # the two parts of the same batch on their own
+        c0 = int(m.chunk_len[0])
+        only_prefill = wl.PrefillBatch("cfg5_prefill_part", m.h_q, m.h_kv, m.d, m.prefix_len[:1],
+                                       m.chunk_len[:1], m.page_table, m.page_table_offs[:2],
+                                       m.num_pages, m.q[:c0].contiguous(), m.k_pool, m.v_pool,
+                                       m.scale)
+        only_decode = wl.PrefillBatch("cfg5_decode_part", m.h_q, m.h_kv, m.d, m.prefix_len[1:],
+                                      m.chunk_len[1:], m.page_table, m.page_table_offs[1:],
+                                      m.num_pages, m.q[c0:].contiguous(), m.k_pool, m.v_pool,
+                                      m.scale)
+        run_p, _, _ = prefill_runner(only_prefill)
+        tp = time_calls(run_p, n_mixed, 2)
+        run_d, _, _ = prefill_runner(only_decode)
+        td = time_calls(run_d, max(10, n_mixed), 3)
+        log(f"mixed: {t['event_ms_mean']:.3f} ms together; prefill part alone "
+            f"{tp['event_ms_mean']:.3f} ms ({pf / (tp['event_ms_mean'] * 1e-3) / 1e12:.0f} TFLOP/s), "
+            f"64 decodes alone {td['event_ms_mean']:.4f} ms "
+            f"({dec_bytes / (td['event_ms_mean'] * 1e-3) / 1e9:.0f} GB/s)")
         result["mixed"] = {
             "workload": "cfg5: prefill chunk 1024 @ prefix 524,288 + 64 decodes "
                         "(log-normal lengths, median 2048, sigma 1.0, clip [256,16384]), one call",
             "ms": t["event_ms_mean"], "prefill_flops": pf, "decode_kv_bytes": dec_bytes,
             "tflops_whole_call": (pf + 4.0 * m.d * m.h_q * float(m.meta["decode_lens"].sum()))
-            / (t["event_ms_mean"] * 1e-3) / 1e12}
+            / (t["event_ms_mean"] * 1e-3) / 1e12,
+            "prefill_part_alone_ms": tp["event_ms_mean"],
+            "prefill_part_alone_tflops": pf / (tp["event_ms_mean"] * 1e-3) / 1e12,
+            "decode_part_alone_ms": td["event_ms_mean"],
+            "decode_part_alone_gbps": dec_bytes / (td["event_ms_mean"] * 1e-3) / 1e9}
+        del only_prefill, only_decode, run_p, run_d
         del m, run
         torch.cuda.empty_cache()
 

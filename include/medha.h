@@ -179,6 +179,32 @@ int medha_describe_plan(const int32_t* prefix_len, const int32_t* chunk_len, int
 int medha_describe_slot(int32_t slot, int32_t num_kv_heads, int32_t n_split, int32_t n_row_tiles,
                         int32_t* kv_head, int32_t* split, int32_t* row_tile);
 
+/*
+ * Yardsticks for the measurement harness (not part of the attention path): what
+ * the device at hand sustains when it does nothing but bf16 matrix instructions,
+ * and nothing but streaming reads, to set beside the data-sheet peaks the
+ * roofline uses.  Both only enqueue one kernel on hip_stream.
+ *
+ * medha_ceiling_mfma_bf16: `blocks` workgroups of 512 threads; every wavefront
+ * chains `iters` rounds of 4 independent 32x32x16 bf16 matrix instructions on
+ * operands taken from `operands` (device, 16-byte aligned, at least 5120 bytes
+ * of bf16 values of the caller's choice: switching power depends on the data).
+ * Work done: blocks * 8 * iters * 4 * 32768 flop.  `sink` (device, at least
+ * blocks * 512 floats) receives checksums.
+ *
+ * medha_ceiling_stream_read: `blocks` workgroups of 256 threads read `bytes`
+ * (a multiple of 16) from `src` once, 16 bytes per lane per load; `sink` (device,
+ * 16-byte aligned, at least blocks * 4096 bytes) receives checksums.
+ *
+ * Errors: MEDHA_ERR_INVALID_ARG for null / misaligned / non-positive arguments,
+ * MEDHA_ERR_WORKSPACE for a sink that is too small, MEDHA_ERR_HIP for a failed launch.
+ */
+int medha_ceiling_mfma_bf16(const void* operands, size_t operand_bytes, int32_t blocks,
+                            int32_t iters, float* sink, size_t sink_floats, void* hip_stream);
+
+int medha_ceiling_stream_read(const void* src, size_t bytes, int32_t blocks, void* sink,
+                              size_t sink_bytes, void* hip_stream);
+
 /* Static, human-readable text for a return code. */
 const char* medha_strerror(int code);
 

@@ -6,6 +6,8 @@ The library is loaded on first use and a missing library is an error.
 """
 from .binding import (  # noqa: F401
     MedhaError,
+    ceiling_mfma_bf16,
+    ceiling_stream_read,
     chunked_prefill_attn,
     chunked_prefill_workspace_bytes,
     decode_partial_attn,

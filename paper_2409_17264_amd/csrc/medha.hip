@@ -8,6 +8,7 @@
 #include <cstring>
 #include <vector>
 
+#include "ceiling_kernels.h"
 #include "common.h"
 #include "decode_kernel.h"
 #include "merge_kernel.h"
@@ -316,6 +317,30 @@ int medha_lse_merge(const float* out_partial, const float* lse_partial, int32_t 
   hipLaunchKernelGGL(lse_merge_kernel, dim3((unsigned)grid), dim3(kThreads), 0,
                      static_cast<hipStream_t>(hip_stream), out_partial, lse_partial, num_splits,
                      rows, num_q_heads, head_dim, out, lse);
+  return hipGetLastError() == hipSuccess ? MEDHA_OK : MEDHA_ERR_HIP;
+}
+
+int medha_ceiling_mfma_bf16(const void* operands, size_t operand_bytes, int32_t blocks,
+                            int32_t iters, float* sink, size_t sink_floats, void* hip_stream) {
+  if (operands == nullptr || sink == nullptr || blocks <= 0 || iters <= 0)
+    return MEDHA_ERR_INVALID_ARG;
+  if (!aligned(operands, 16) || operand_bytes < 5 * 64 * 16) return MEDHA_ERR_INVALID_ARG;
+  if (sink_floats < (size_t)blocks * 512) return MEDHA_ERR_WORKSPACE;
+  hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(blocks), dim3(512), 0,
+                     static_cast<hipStream_t>(hip_stream),
+                     static_cast<const uint4*>(operands), iters, sink);
+  return hipGetLastError() == hipSuccess ? MEDHA_OK : MEDHA_ERR_HIP;
+}
+
+int medha_ceiling_stream_read(const void* src, size_t bytes, int32_t blocks, void* sink,
+                              size_t sink_bytes, void* hip_stream) {
+  if (src == nullptr || sink == nullptr || blocks <= 0 || bytes % 16 != 0)
+    return MEDHA_ERR_INVALID_ARG;
+  if (!aligned(src, 16) || !aligned(sink, 16)) return MEDHA_ERR_INVALID_ARG;
+  if (sink_bytes < (size_t)blocks * 256 * 16) return MEDHA_ERR_WORKSPACE;
+  hipLaunchKernelGGL(read_ceiling_kernel, dim3(blocks), dim3(256), 0,
+                     static_cast<hipStream_t>(hip_stream), static_cast<const u32x4*>(src),
+                     bytes / 16, static_cast<u32x4*>(sink));
   return hipGetLastError() == hipSuccess ? MEDHA_OK : MEDHA_ERR_HIP;
 }
 

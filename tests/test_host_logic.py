@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "medha.h")).read()
     body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)          # drop comments
-    declared = set(re.findall(r"\b(medha_[a-z_]+)\s*\(", body))
+    declared = set(re.findall(r"\b(medha_[a-z0-9_]+)\s*\(", body))
     assert declared == set(binding.EXPORTS), declared ^ set(binding.EXPORTS)
     lib = medha.load_library()
     for name in declared:
