@@ -13,6 +13,8 @@ The same JSON line also carries, each measured in its own timed loop:
            merge): KV-read GB/s against the HBM roofline;
   sweep    the Llama-3-70B tensor-parallel share (8 q / 1 kv head, 1M prefix)
            at chunk sizes 512..8192: TFLOP/s per chunk size;
+  append   the chunk's K/V scattered into the paged pools (the step before the
+           attention call): microseconds and GB/s;
   mixed    one 1024-token prefill chunk at a 524,288-token prefix plus 64
            decodes in one call.
   ceilings what the same device sustains, in the same run, on an MFMA-only loop
@@ -22,7 +24,7 @@ and `cpu_baseline`: the fp64 CPU oracle timed on a bounded sample of rows of
 the headline workload on this machine's host cores (a reported baseline only).
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W]
-                [--sections ceilings,main,decode,sweep,mixed,cpu[,copy]]
+                [--sections ceilings,main,append,decode,sweep,mixed,cpu[,copy]]
 """
 import argparse
 import json
@@ -133,7 +135,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--sections", default="ceilings,main,decode,sweep,mixed,cpu")
+    ap.add_argument("--sections", default="ceilings,main,append,decode,sweep,mixed,cpu")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (KV-cache parallelism is exercised "
@@ -219,6 +221,26 @@ def main():
         log(f"cpu oracle: {result['cpu_baseline']}")
     del b, run, out, lse
     torch.cuda.empty_cache()
+
+    # --------------------------------------------------------------- append
+    if "append" in sections:
+        # the step before attention: the chunk's K/V written into the paged pools
+        a = wl.config2_llama8b("cuda:0")
+        c0, p0 = int(a.chunk_len[0]), int(a.prefix_len[0])
+        k_new = torch.randn(c0, a.h_kv, a.d, device="cuda").to(torch.bfloat16)
+        v_new = torch.randn(c0, a.h_kv, a.d, device="cuda").to(torch.bfloat16)
+        pt_a = torch.from_numpy(a.page_table).cuda()
+        t = time_calls(lambda: medha.kv_append(k_new, v_new, a.k_pool, a.v_pool, pt_a,
+                                               a.page_table_offs, [p0], [c0]), args.steps, 5)
+        moved = 2.0 * 2 * k_new.numel() * 2          # K and V, read + written
+        log(f"append: {t['event_ms_mean'] * 1e3:.1f} us for {c0} tokens -> "
+            f"{moved / (t['event_ms_mean'] * 1e-3) / 1e9:.0f} GB/s read+write")
+        result["append"] = {"workload": "cfg2's chunk: 2048 tokens x 8 kv heads x d 128 into the "
+                                        "paged pools at positions 32768..34815",
+                            "us": t["event_ms_mean"] * 1e3, "bytes_read_plus_written": moved,
+                            "gbps": moved / (t["event_ms_mean"] * 1e-3) / 1e9}
+        del a, k_new, v_new, pt_a
+        torch.cuda.empty_cache()
 
     # --------------------------------------------------------------- decode
     if "decode" in sections:

@@ -56,7 +56,8 @@ extern "C" {
 #define MEDHA_ERR_WORKSPACE (-3)    /* workspace missing, misaligned or too small              */
 #define MEDHA_ERR_HIP (-4)          /* a HIP runtime call failed                               */
 
-/* Paged KV cache descriptor (host struct holding device pointers).  Read-only. */
+/* Paged KV cache descriptor (host struct holding device pointers).  The pools are read-only
+ * for every call except medha_kv_append. */
 typedef struct medha_kv_cache {
   const void* k_pool; /* dev bf16 [num_pages][num_kv_heads][page_size][head_dim], 16-byte aligned */
   const void* v_pool; /* dev bf16, same shape                                                    */
@@ -147,6 +148,29 @@ size_t medha_decode_partial_workspace_bytes(const int32_t* kv_len, int32_t items
  */
 int medha_lse_merge(const float* out_partial, const float* lse_partial, int32_t num_splits,
                     int64_t rows, int32_t num_q_heads, int32_t head_dim, float* out, float* lse,
+                    void* hip_stream);
+
+/*
+ * KV-cache append (paper section 3.1: the keys and values of every chunk join
+ * the paged cache that all later chunks and decode steps read; the attention
+ * calls above expect them there).  Token j of sequence b, row
+ * sum(chunk_len[0..b)) + j of k_new / v_new, is written to position
+ * prefix_len[b] + j of the sequence: page page_table[offs[b] + position / 16],
+ * slot position % 16, all KV heads.  A bit-exact copy; nothing else in the pools
+ * is touched.  This is the one call that WRITES kv->k_pool / kv->v_pool.
+ *
+ *   k_new, v_new     dev  bf16 [sum chunk_len][num_kv_heads][head_dim], 16-byte aligned
+ *   page_table, page_table_offs, prefix_len, chunk_len, batch: as for
+ *                    medha_chunked_prefill_attn (same arrays can be passed to both)
+ *
+ * A page-table entry outside [0, kv->num_pages) is skipped on the device (that
+ * token is not written); pages shared by two sequences of the batch are the
+ * caller's error and give an unspecified winner.  No workspace, no allocation;
+ * batches of more than 64 sequences take several kernel launches.
+ */
+int medha_kv_append(const void* k_new, const void* v_new, const medha_kv_cache* kv,
+                    const int32_t* page_table, const int64_t* page_table_offs,
+                    const int32_t* prefix_len, const int32_t* chunk_len, int32_t batch,
                     void* hip_stream);
 
 /*

@@ -121,3 +121,27 @@ def lse_merge(out_partial, lse_partial):
     if rc != 0:
         raise ValueError(f"oracle lse_merge failed with code {rc}")
     return out, lse
+
+
+def kv_append(k_new, v_new, k_pool, v_pool, page_table, page_table_offs, prefix_len, chunk_len):
+    """The definition of the cache append, token by token (paper section 3.1: a chunk's keys
+    and values join the paged cache): token j of sequence b, row sum(chunk_len[:b]) + j of the
+    new arrays, lands at position prefix_len[b] + j, i.e. page
+    page_table[offs[b] + position // page_size], slot position % page_size, for every KV head.
+
+    k_new, v_new uint16 [tokens][h_kv][d]; pools uint16 [pages][h_kv][page_size][d] are
+    modified IN PLACE (and returned).  Plain Python loop: meant for test-sized inputs.
+    """
+    assert k_pool.dtype == np.uint16 and v_pool.dtype == np.uint16
+    assert k_new.shape == v_new.shape and k_pool.shape == v_pool.shape
+    page_size = k_pool.shape[2]
+    row = 0
+    for b in range(len(prefix_len)):
+        for j in range(int(chunk_len[b])):
+            position = int(prefix_len[b]) + j
+            page = int(page_table[int(page_table_offs[b]) + position // page_size])
+            slot = position % page_size
+            k_pool[page, :, slot, :] = k_new[row]
+            v_pool[page, :, slot, :] = v_new[row]
+            row += 1
+    return k_pool, v_pool

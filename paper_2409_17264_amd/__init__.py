@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     decode_partial_workspace_bytes,
     describe_plan,
     describe_slot,
+    kv_append,
     library_path,
     load_library,
     lse_merge,

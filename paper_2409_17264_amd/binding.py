@@ -23,6 +23,7 @@ EXPORTS = (
     "medha_decode_partial_attn",
     "medha_decode_partial_workspace_bytes",
     "medha_lse_merge",
+    "medha_kv_append",
     "medha_describe_plan",
     "medha_describe_slot",
     "medha_ceiling_mfma_bf16",
@@ -78,6 +79,8 @@ def load_library():
     lib.medha_decode_partial_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
     lib.medha_lse_merge.restype = ctypes.c_int
     lib.medha_lse_merge.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp]
+    lib.medha_kv_append.restype = ctypes.c_int
+    lib.medha_kv_append.argtypes = [vp, vp, ctypes.POINTER(_KvCache), vp, vp, vp, vp, i32, vp]
     lib.medha_describe_plan.restype = ctypes.c_int
     lib.medha_describe_plan.argtypes = [vp, vp, i32, i32, i32, i32, i32, ctypes.POINTER(PlanEntry),
                                         ctypes.POINTER(i32), ctypes.POINTER(i32),
@@ -252,6 +255,27 @@ def lse_merge(out_partial: torch.Tensor, lse_partial: torch.Tensor,
     _check(lib.medha_lse_merge(_dp(out_partial), _dp(lse_partial), s, rows, h_q, d, _dp(out),
                                _dp(lse), _stream()))
     return out, lse
+
+
+def kv_append(k_new: torch.Tensor, v_new: torch.Tensor, k_pool: torch.Tensor,
+              v_pool: torch.Tensor, page_table: torch.Tensor, page_table_offs, prefix_len,
+              chunk_len) -> None:
+    """k_new, v_new bf16 [tokens][h_kv][d] (device) are written into the pools in place."""
+    lib = load_library()
+    for t in (k_new, v_new):
+        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.dim() == 3
+    assert k_new.shape == v_new.shape
+    assert page_table.is_cuda and page_table.dtype == torch.int32 and page_table.is_contiguous()
+    kv = _kv(k_pool, v_pool)
+    tokens, h_kv, d = k_new.shape
+    assert h_kv == kv.num_kv_heads and d == kv.head_dim
+    offs = _host(page_table_offs, np.int64)
+    pre, chk = _host(prefix_len, np.int32), _host(chunk_len, np.int32)
+    batch = len(pre)
+    assert len(chk) == batch and len(offs) == batch + 1 and int(chk.sum()) == tokens
+    assert int(offs[-1]) <= page_table.numel()
+    _check(lib.medha_kv_append(_dp(k_new), _dp(v_new), ctypes.byref(kv), _dp(page_table),
+                               _hp(offs), _hp(pre), _hp(chk), batch, _stream()))
 
 
 def ceiling_mfma_bf16(operands: torch.Tensor, blocks: int, iters: int, sink: torch.Tensor) -> float:

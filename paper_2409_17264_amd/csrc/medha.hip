@@ -8,6 +8,7 @@
 #include <cstring>
 #include <vector>
 
+#include "append_kernel.h"
 #include "ceiling_kernels.h"
 #include "common.h"
 #include "decode_kernel.h"
@@ -318,6 +319,66 @@ int medha_lse_merge(const float* out_partial, const float* lse_partial, int32_t 
                      static_cast<hipStream_t>(hip_stream), out_partial, lse_partial, num_splits,
                      rows, num_q_heads, head_dim, out, lse);
   return hipGetLastError() == hipSuccess ? MEDHA_OK : MEDHA_ERR_HIP;
+}
+
+int medha_kv_append(const void* k_new, const void* v_new, const medha_kv_cache* kv,
+                    const int32_t* page_table, const int64_t* page_table_offs,
+                    const int32_t* prefix_len, const int32_t* chunk_len, int32_t batch,
+                    void* hip_stream) {
+  if (kv == nullptr || batch < 0) return MEDHA_ERR_INVALID_ARG;
+  if (kv->num_kv_heads <= 0 || kv->num_pages < 0) return MEDHA_ERR_INVALID_ARG;
+  if (kv->page_size != kPageSize || (kv->head_dim != 64 && kv->head_dim != 128))
+    return MEDHA_ERR_UNSUPPORTED;
+  if (batch == 0) return MEDHA_OK;
+  if (k_new == nullptr || v_new == nullptr || kv->k_pool == nullptr || kv->v_pool == nullptr ||
+      page_table == nullptr || page_table_offs == nullptr || prefix_len == nullptr ||
+      chunk_len == nullptr)
+    return MEDHA_ERR_INVALID_ARG;
+  if (!aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(kv->k_pool, 16) ||
+      !aligned(kv->v_pool, 16))
+    return MEDHA_ERR_INVALID_ARG;
+  int64_t rows = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (prefix_len[b] < 0 || chunk_len[b] < 1) return MEDHA_ERR_INVALID_ARG;
+    const int64_t pages = ceil_div((int64_t)prefix_len[b] + chunk_len[b], kPageSize);
+    if (page_table_offs[b] < 0 || page_table_offs[b + 1] - page_table_offs[b] < pages)
+      return MEDHA_ERR_INVALID_ARG;
+    rows += chunk_len[b];
+    if (rows > INT32_MAX) return MEDHA_ERR_INVALID_ARG;
+  }
+  // validated in full before the first launch; up to kMaxInlineSeq sequences per launch
+  int64_t src_row = 0;
+  for (int b0 = 0; b0 < batch; b0 += kMaxInlineSeq) {
+    AppendArgs a{};
+    a.k_new = static_cast<const uint4*>(k_new);
+    a.v_new = static_cast<const uint4*>(v_new);
+    a.k_pool = static_cast<uint4*>(const_cast<void*>(kv->k_pool));
+    a.v_pool = static_cast<uint4*>(const_cast<void*>(kv->v_pool));
+    a.page_table = page_table;
+    a.h_kv = kv->num_kv_heads;
+    a.words_per_row = kv->head_dim / 8;
+    a.num_pages = kv->num_pages;
+    a.n_seq = std::min(kMaxInlineSeq, batch - b0);
+    int32_t rank = 0;
+    for (int i = 0; i < a.n_seq; ++i) {
+      AppendDesc& sd = a.descs[i];
+      sd.pt_off = page_table_offs[b0 + i];
+      sd.src_row = (int32_t)src_row;
+      sd.prefix_len = prefix_len[b0 + i];
+      sd.chunk_len = chunk_len[b0 + i];
+      sd.row_rank = rank;
+      rank += sd.chunk_len;
+      src_row += sd.chunk_len;
+    }
+    a.total_rows = rank;
+    const int64_t threads = (int64_t)rank * a.h_kv * a.words_per_row;
+    const int64_t grid = ceil_div(threads, kThreads);
+    if (grid > INT32_MAX) return MEDHA_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)grid), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(hip_stream), a);
+    if (hipGetLastError() != hipSuccess) return MEDHA_ERR_HIP;
+  }
+  return MEDHA_OK;
 }
 
 int medha_ceiling_mfma_bf16(const void* operands, size_t operand_bytes, int32_t blocks,

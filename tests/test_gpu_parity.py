@@ -259,3 +259,72 @@ def test_invalid_arguments_are_rejected_without_writing():
     assert e.value.code == -3
     torch.cuda.synchronize()
     assert bool((out == 7.0).all()) and bool((lse == 7.0).all())
+
+
+# ------------------------------------------------------------------- KV append
+@pytest.mark.parametrize("h_kv,d,n_seq", [(2, 64, 1), (8, 128, 5), (1, 128, 70)])
+def test_kv_append_is_bit_exact(h_kv, d, n_seq):
+    """Pools after the GPU append equal the pools after the oracle's append, bit for bit:
+    every new row in its (page, slot), nothing else touched.  70 sequences take two launches."""
+    rng = np.random.default_rng(h_kv * 100 + n_seq)
+    prefix = rng.integers(0, 70, n_seq).astype(np.int32)
+    chunk = rng.integers(1, 50, n_seq).astype(np.int32)
+    prefix[0], chunk[0] = 0, 1
+    pages_per = (prefix + chunk + 15) // 16
+    num_pages = int(pages_per.sum()) + 5
+    offs = np.concatenate([[0], np.cumsum(pages_per)]).astype(np.int64)
+    pt = rng.permutation(num_pages).astype(np.int32)[:offs[-1]]
+    k_pool = rng.integers(0, 1 << 16, (num_pages, h_kv, 16, d)).astype(np.uint16)
+    v_pool = rng.integers(0, 1 << 16, (num_pages, h_kv, 16, d)).astype(np.uint16)
+    tokens = int(chunk.sum())
+    k_new = rng.integers(0, 1 << 16, (tokens, h_kv, d)).astype(np.uint16)
+    v_new = rng.integers(0, 1 << 16, (tokens, h_kv, d)).astype(np.uint16)
+
+    def dev(a):
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    kp, vp = dev(k_pool), dev(v_pool)
+    medha.kv_append(dev(k_new), dev(v_new), kp, vp, torch.from_numpy(pt).cuda(), offs, prefix,
+                    chunk)
+    torch.cuda.synchronize()
+    oracle.kv_append(k_new, v_new, k_pool, v_pool, pt, offs, prefix, chunk)
+    assert np.array_equal(kp.view(torch.int16).cpu().numpy().view(np.uint16), k_pool)
+    assert np.array_equal(vp.view(torch.int16).cpu().numpy().view(np.uint16), v_pool)
+
+
+def test_kv_append_skips_page_ids_outside_the_pool():
+    h_kv, d = 2, 64
+    k_pool = torch.zeros(4, h_kv, 16, d, dtype=torch.bfloat16, device="cuda")
+    v_pool = torch.zeros_like(k_pool)
+    new = torch.ones(20, h_kv, d, dtype=torch.bfloat16, device="cuda")
+    pt = torch.tensor([2, 1 << 20], dtype=torch.int32, device="cuda")   # second page id is bad
+    medha.kv_append(new, new, k_pool, v_pool, pt, [0, 2], [0], [20])
+    torch.cuda.synchronize()
+    assert float(k_pool[2].float().sum()) == 16 * h_kv * d              # first 16 tokens landed
+    assert float(k_pool.float().sum()) == 16 * h_kv * d                 # the other 4 went nowhere
+
+
+def test_chunk_by_chunk_prefill_on_the_gpu_equals_one_shot_oracle():
+    """End to end on the device: empty (NaN) cache, then per chunk append + attention; all rows
+    against the oracle's one-shot causal pass over the full cache."""
+    n = 1500
+    full = wl.make_prefill_batch("e2e", 8, 2, 128, [0], [n], seed=77)
+    ro, rl = oracle_prefill(full)
+    pages = full.page_table[:(n + 15) // 16].astype(np.int64)
+    k_seq = full.k_pool[pages].permute(0, 2, 1, 3).reshape(-1, 2, 128)[:n].contiguous().cuda()
+    v_seq = full.v_pool[pages].permute(0, 2, 1, 3).reshape(-1, 2, 128)[:n].contiguous().cuda()
+    k_live = torch.full_like(full.k_pool, float("nan")).cuda()
+    v_live = torch.full_like(full.v_pool, float("nan")).cuda()
+    pt = torch.from_numpy(full.page_table).cuda()
+    q = full.q.cuda()
+    outs, lses, start = [], [], 0
+    for c in [1, 300, 17, 512, 70, 600]:
+        medha.kv_append(k_seq[start:start + c], v_seq[start:start + c], k_live, v_live, pt,
+                        full.page_table_offs, [start], [c])
+        o, l = medha.chunked_prefill_attn(q[start:start + c].contiguous(), k_live, v_live, pt,
+                                          full.page_table_offs, [start], [c], full.scale)
+        outs.append(o)
+        lses.append(l)
+        start += c
+    assert start == n
+    torch.cuda.synchronize()
+    check(torch.cat(outs).cpu().numpy(), torch.cat(lses).cpu().numpy(), ro, rl, "chunk-by-chunk")

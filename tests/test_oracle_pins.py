@@ -299,3 +299,73 @@ def test_workload_shapes_match_named_configs():
     big = wl.lognormal_lengths(20000, 1)
     assert abs(np.median(big) - 2048) < 80
     assert 4.0 * 128 * 32 * (2048 * 32768 + 2048 * 2049 / 2) == pytest.approx(1.134e12, rel=2e-3)
+
+
+# KV append -------------------------------------------------------------------
+def _append_case(seed, h_kv=2, d=32, seqs=((0, 5), (13, 20), (16, 16), (31, 2))):
+    """Pools filled with a recognisable background, a page table over a shuffled pool,
+    and new K/V rows for every sequence's chunk."""
+    rng = np.random.default_rng(seed)
+    prefix = np.array([s[0] for s in seqs], np.int32)
+    chunk = np.array([s[1] for s in seqs], np.int32)
+    pages_per = [(int(p) + int(c) + 15) // 16 for p, c in seqs]
+    num_pages = sum(pages_per) + 3
+    perm = rng.permutation(num_pages).astype(np.int32)
+    offs = np.concatenate([[0], np.cumsum(pages_per)]).astype(np.int64)
+    pt = perm[:offs[-1]].copy()
+    k_pool = rng.integers(0, 1 << 16, (num_pages, h_kv, 16, d)).astype(np.uint16)
+    v_pool = rng.integers(0, 1 << 16, (num_pages, h_kv, 16, d)).astype(np.uint16)
+    tokens = int(chunk.sum())
+    k_new = rng.integers(0, 1 << 16, (tokens, h_kv, d)).astype(np.uint16)
+    v_new = rng.integers(0, 1 << 16, (tokens, h_kv, d)).astype(np.uint16)
+    return k_new, v_new, k_pool, v_pool, pt, offs, prefix, chunk
+
+
+def test_append_then_gather_returns_the_rows_and_touches_nothing_else():
+    """Reading the sequence back through the page table (the gather the attention oracle's
+    brute force uses, written independently) returns exactly the appended rows at positions
+    prefix .. prefix+chunk-1, and every other slot of both pools keeps its bits."""
+    k_new, v_new, k_pool, v_pool, pt, offs, prefix, chunk = _append_case(3)
+    k0, v0 = k_pool.copy(), v_pool.copy()
+    oracle.kv_append(k_new, v_new, k_pool, v_pool, pt, offs, prefix, chunk)
+    touched = np.zeros(k_pool.shape[:1] + k_pool.shape[2:3], bool)      # [page][slot]
+    row = 0
+    for b in range(len(prefix)):
+        n = int(prefix[b] + chunk[b])
+        pages = pt[offs[b]:offs[b] + (n + 15) // 16]
+        for pool, new in ((k_pool, k_new), (v_pool, v_new)):
+            seq = pool[pages].transpose(1, 0, 2, 3).reshape(pool.shape[1], -1, pool.shape[3])
+            got = seq[:, prefix[b]:n].transpose(1, 0, 2)                 # [chunk][h_kv][d]
+            assert np.array_equal(got, new[row:row + chunk[b]])
+        for t in range(int(prefix[b]), n):
+            touched[pages[t // 16], t % 16] = True
+        row += int(chunk[b])
+    keep = ~touched
+    assert np.array_equal(k_pool.transpose(0, 2, 1, 3)[keep], k0.transpose(0, 2, 1, 3)[keep])
+    assert np.array_equal(v_pool.transpose(0, 2, 1, 3)[keep], v0.transpose(0, 2, 1, 3)[keep])
+    assert touched.sum() == chunk.sum()
+
+
+def test_chunk_by_chunk_append_and_attention_equals_one_shot():
+    """The use the append exists for: start from an EMPTY (poisoned) cache, append each chunk's
+    K/V and attend, chunk after chunk; every row equals the one-shot causal pass over the
+    fully populated cache bit for bit."""
+    n = 90
+    full = wl.make_prefill_batch("t", 4, 2, 32, [0], [n], seed=33)
+    q, k, v = _np(full)
+    fo, fl = _run(full)
+    k_live = np.full_like(k, 0x7FC0)          # bf16 NaN everywhere
+    v_live = np.full_like(v, 0x7FC0)
+    pages = full.page_table[:(n + 15) // 16]
+    k_seq = k[pages].transpose(0, 2, 1, 3).reshape(-1, k.shape[1], k.shape[3])   # [pos][h][d]
+    v_seq = v[pages].transpose(0, 2, 1, 3).reshape(-1, v.shape[1], v.shape[3])
+    start = 0
+    for c in [3, 13, 16, 1, 40, 17]:
+        oracle.kv_append(k_seq[start:start + c], v_seq[start:start + c], k_live, v_live,
+                         full.page_table, full.page_table_offs, [start], [c])
+        o, l = oracle.chunked_prefill_attn(q[start:start + c], k_live, v_live, full.page_table,
+                                           full.page_table_offs, [start], [c], full.scale)
+        assert np.array_equal(o, fo[start:start + c])
+        assert np.array_equal(l, fl[start:start + c])
+        start += c
+    assert start == n
