@@ -29,6 +29,9 @@ def _lib():
         lib.medha_oracle_decode_partial.restype = ctypes.c_int
         lib.medha_oracle_decode_partial.argtypes = [
             vp, i32, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, i32, i32, f64, vp, vp]
+        lib.medha_oracle_chunk_partial.restype = ctypes.c_int
+        lib.medha_oracle_chunk_partial.argtypes = [
+            vp, i32, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, i32, i32, f64, vp, vp]
         lib.medha_oracle_lse_merge.restype = ctypes.c_int
         lib.medha_oracle_lse_merge.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp]
         lib.medha_oracle_num_threads.restype = ctypes.c_int
@@ -104,6 +107,39 @@ def decode_partial_attn(q, k_pool, v_pool, page_table, page_table_offs, q_index,
         float(scale), out.ctypes.data_as(ctypes.c_void_p), lse.ctypes.data_as(ctypes.c_void_p))
     if rc != 0:
         raise ValueError(f"oracle decode_partial failed with code {rc}")
+    return out, lse
+
+
+def chunk_partial_attn(q, k_pool, v_pool, page_table, page_table_offs, q_row, chunk_len, kv_len,
+                       visible0, scale):
+    """Item i: query rows q_row[i] .. +chunk_len[i] of q (uint16 [tokens][h_q][d]) against the
+    kv_len[i] keys of its page-table slice; row j sees the first
+    min(kv_len, max(0, visible0[i] + j)) of them.
+    Returns (out [sum chunk_len][h_q][d], lse [sum chunk_len][h_q])."""
+    q, qp = _arr(q, np.uint16)
+    k_pool, kp = _arr(k_pool, np.uint16)
+    v_pool, vpp = _arr(v_pool, np.uint16)
+    tokens, h_q, d = q.shape
+    num_pages, h_kv, page_size, d2 = k_pool.shape
+    assert d2 == d and k_pool.shape == v_pool.shape
+    pt, ptp = _arr(page_table, np.int32)
+    offs, offp = _arr(page_table_offs, np.int64)
+    qr, qrp = _arr(q_row, np.int32)
+    chk, chkp = _arr(chunk_len, np.int32)
+    kl, klp = _arr(kv_len, np.int32)
+    v0, v0p = _arr(visible0, np.int32)
+    items = qr.shape[0]
+    assert chk.shape[0] == items and kl.shape[0] == items and v0.shape[0] == items
+    assert offs.shape[0] == items + 1 and int(offs[-1]) <= pt.shape[0]
+    rows = int(chk.sum())
+    out = np.empty((rows, h_q, d), np.float64)
+    lse = np.empty((rows, h_q), np.float64)
+    rc = _lib().medha_oracle_chunk_partial(
+        qp, tokens, kp, vpp, num_pages, page_size, h_kv, d, ptp, offp, qrp, chkp, klp, v0p, items,
+        h_q, float(scale), out.ctypes.data_as(ctypes.c_void_p),
+        lse.ctypes.data_as(ctypes.c_void_p))
+    if rc != 0:
+        raise ValueError(f"oracle chunk_partial failed with code {rc}")
     return out, lse
 
 

@@ -205,6 +205,86 @@ int medha_oracle_decode_partial(const uint16_t *q, int32_t num_queries, const ui
 }
 
 /*
+ * KV-cache-parallel partial of a prefill CHUNK (paper section 3.3: the query that is
+ * replicated to the KV shards is "either a decode token or a prefill chunk").  Item i is
+ * (chunk, shard): query rows q_row[i] .. q_row[i] + chunk_len[i] - 1 of q against the
+ * paged key slice of kv_len[i] keys given by the item's page-table slice.  Row j of the
+ * chunk sees the first  min(kv_len, max(0, visible0[i] + j))  keys of the slice: a shard
+ * that lies wholly before the chunk has visible0 >= kv_len (no mask); the shard that
+ * holds the chunk's own keys has visible0 = (chunk's first position) - (shard's first
+ * position) + 1; rows with no visible key yield O = 0, LSE = -inf.
+ * out_partial [sum chunk_len][h_q][d], lse_partial [sum chunk_len][h_q], items in order.
+ */
+int medha_oracle_chunk_partial(const uint16_t *q, int32_t num_tokens, const uint16_t *k_pool,
+                               const uint16_t *v_pool, int32_t num_pages, int32_t page_size,
+                               int32_t h_kv, int32_t d, const int32_t *page_table,
+                               const int64_t *page_table_offs, const int32_t *q_row,
+                               const int32_t *chunk_len, const int32_t *kv_len,
+                               const int32_t *visible0, int32_t items, int32_t h_q,
+                               double scale, double *out_partial, double *lse_partial) {
+    if (items < 0 || h_q <= 0 || h_kv <= 0 || d <= 0 || page_size <= 0 || h_q % h_kv != 0)
+        return -1;
+    int64_t max_keys = 0, total_rows = 0;
+    for (int32_t i = 0; i < items; ++i) {
+        if (kv_len[i] < 0 || chunk_len[i] < 1 || q_row[i] < 0 ||
+            (int64_t)q_row[i] + chunk_len[i] > num_tokens)
+            return -1;
+        int64_t pages_needed = ((int64_t)kv_len[i] + page_size - 1) / page_size;
+        if (page_table_offs[i + 1] - page_table_offs[i] < pages_needed) return -1;
+        if (kv_len[i] > max_keys) max_keys = kv_len[i];
+        total_rows += chunk_len[i];
+    }
+    /* (item, row in chunk) of every output row */
+    int32_t *row_item = (int32_t *)malloc(sizeof(int32_t) * (size_t)(total_rows > 0 ? total_rows : 1));
+    int32_t *row_j = (int32_t *)malloc(sizeof(int32_t) * (size_t)(total_rows > 0 ? total_rows : 1));
+    if (row_item == NULL || row_j == NULL) {
+        free(row_item);
+        free(row_j);
+        return -3;
+    }
+    int64_t r = 0;
+    for (int32_t i = 0; i < items; ++i)
+        for (int32_t j = 0; j < chunk_len[i]; ++j, ++r) {
+            row_item[r] = i;
+            row_j[r] = j;
+        }
+    int32_t group = h_q / h_kv;
+    int status = 0;
+    int64_t n_units = total_rows * h_q;
+#pragma omp parallel
+    {
+        double *scratch = (double *)malloc(sizeof(double) * (size_t)(max_keys > 0 ? max_keys : 1));
+        /* every thread reaches the loop below; one without scratch only reports */
+        {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t u = 0; u < n_units; ++u) {
+                int64_t row = u / h_q;
+                int32_t h = (int32_t)(u % h_q);
+                int32_t i = row_item[row], j = row_j[row];
+                int64_t n_keys = (int64_t)visible0[i] + j;
+                if (n_keys < 0) n_keys = 0;
+                if (n_keys > kv_len[i]) n_keys = kv_len[i];
+                int rc = -3;
+                if (scratch != NULL)
+                    rc = attend_one(q + ((int64_t)(q_row[i] + j) * h_q + h) * d, k_pool, v_pool,
+                                    num_pages, page_size, h_kv, d, h / group,
+                                    page_table + page_table_offs[i], n_keys, scale, scratch,
+                                    out_partial + (row * h_q + h) * (int64_t)d,
+                                    lse_partial + row * h_q + h);
+                if (rc != 0) {
+#pragma omp atomic write
+                    status = rc;
+                }
+            }
+        }
+        free(scratch);
+    }
+    free(row_item);
+    free(row_j);
+    return status;
+}
+
+/*
  * Merge of num_splits partial results over disjoint key sets:
  *   LSE = ln sum_s exp(LSE_s),   O = sum_s exp(LSE_s - LSE) O_s.
  * Partials with LSE_s = -inf (no keys) carry weight zero; if every partial is

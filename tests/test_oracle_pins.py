@@ -369,3 +369,69 @@ def test_chunk_by_chunk_append_and_attention_equals_one_shot():
         assert np.array_equal(l, fl[start:start + c])
         start += c
     assert start == n
+
+
+# chunk partial (KV-cache parallelism for a prefill chunk) ----------------------
+def _shard_items(b, cuts, prefix, chunk):
+    """Items (page-table slices, kv_len, visible0) of one chunk against the page-aligned
+    shards [cuts[i], cuts[i+1]) of its sequence."""
+    pts, pto, kv_len, vis0 = [], [0], [], []
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        assert lo % 16 == 0
+        sl = b.page_table[lo // 16:(hi + 15) // 16]
+        pts.append(sl)
+        pto.append(pto[-1] + len(sl))
+        kv_len.append(hi - lo)
+        vis0.append(prefix + 1 - lo)       # row 0 sees global keys 0..prefix, local 0..prefix-lo
+    return (np.concatenate(pts), np.array(pto, np.int64), np.array(kv_len, np.int32),
+            np.array(vis0, np.int32))
+
+
+@pytest.mark.parametrize("prefix,chunk,cuts", [
+    (40, 9, [0, 16, 32, 49]),              # chunk inside the last shard
+    (40, 30, [0, 48, 64, 70]),             # chunk straddles three shards
+    (0, 33, [0, 16, 33]),                  # no prefix: early rows see nothing of shard 2
+    (100, 1, [0, 64, 101]),                # a decode token is a chunk of one
+])
+def test_chunk_partials_over_shards_merge_to_the_unsplit_result(prefix, chunk, cuts):
+    """KV-cache parallelism for a chunk: per-shard partials + the LSE merge equal plain
+    chunked-prefill attention (itself pinned by the brute force above), also when the chunk
+    straddles shard boundaries and some rows see no key of a shard."""
+    b = wl.make_prefill_batch("kvp", 4, 2, 32, [prefix], [chunk], seed=prefix + chunk)
+    q, k, v = _np(b)
+    ro, rl = _run(b)
+    pt, pto, kv_len, vis0 = _shard_items(b, cuts, prefix, chunk)
+    items = len(kv_len)
+    po, pl = oracle.chunk_partial_attn(q, k, v, pt, pto, np.zeros(items, np.int32),
+                                       np.full(items, chunk, np.int32), kv_len, vis0, b.scale)
+    o, l = oracle.lse_merge(po.reshape(items, chunk, 4, 32), pl.reshape(items, chunk, 4))
+    assert np.max(np.abs(o - ro)) < 1e-12 and np.max(np.abs(l - rl)) < 1e-12
+
+
+def test_chunk_partial_reduces_to_prefill_and_to_decode():
+    """One shard holding everything is chunked prefill, row for row and bit for bit; a fully
+    visible shard is, per row, the decode partial of that row's token."""
+    b = wl.make_prefill_batch("one", 4, 2, 32, [37], [20], seed=9)
+    q, k, v = _np(b)
+    ro, rl = _run(b)
+    o, l = oracle.chunk_partial_attn(q, k, v, b.page_table, b.page_table_offs, [0], [20], [57],
+                                     [38], b.scale)
+    assert np.array_equal(o, ro) and np.array_equal(l, rl)
+    # shard = first 32 keys, visible to every row
+    o, l = oracle.chunk_partial_attn(q, k, v, b.page_table[:2], [0, 2], [0], [20], [32], [1000],
+                                     b.scale)
+    do, dl = oracle.decode_partial_attn(q, k, v, np.tile(b.page_table[:2], 20),
+                                        np.arange(21) * 2, np.arange(20), np.full(20, 32),
+                                        b.scale)
+    assert np.array_equal(o, do) and np.array_equal(l, dl)
+
+
+def test_chunk_partial_rows_without_keys_are_empty():
+    b = wl.make_prefill_batch("e", 2, 1, 32, [0], [8], seed=4)
+    q, k, v = _np(b)
+    # visible0 = -3: rows 0..3 see nothing, row 4 one key, ... row 7 four keys
+    o, l = oracle.chunk_partial_attn(q, k, v, b.page_table, b.page_table_offs, [0], [8], [8],
+                                     [-3], b.scale)
+    assert np.all(o[:4] == 0) and np.all(np.isneginf(l[:4])) and np.all(np.isfinite(l[4:]))
+    vv = bf16_to_f64(v[b.page_table[0], 0])            # [16][d]
+    assert np.allclose(o[4, 0], vv[0], atol=1e-15)     # a single visible key: O is its V row
