@@ -135,6 +135,45 @@ size_t medha_decode_partial_workspace_bytes(const int32_t* kv_len, int32_t items
                                             int32_t head_dim);
 
 /*
+ * KV-cache-parallel partial of a prefill chunk (paper section 3.3: the query that
+ * is replicated to the KV shards is a decode token or a prefill chunk; each shard
+ * computes a partial attention output over its local keys).  Item i is (chunk,
+ * shard): query rows q_row[i] .. q_row[i] + chunk_len[i] - 1 of q against the
+ * kv_len[i] keys of the item's page-table slice (a shard starts on a page
+ * boundary).  Row j of the chunk sees the first
+ *     min(kv_len[i], max(0, visible0[i] + j))
+ * keys of the slice: a shard that lies wholly before the chunk has
+ * visible0 >= kv_len (no mask); for the shard that holds the chunk's own keys,
+ * visible0 = (position of the chunk's first token) - (position of the shard's
+ * first token) + 1.  Rows that see no key of a shard get O = 0, LSE = -inf.
+ * The items' outputs follow each other in item order, so S shards of one chunk
+ * of c rows produce exactly the [S][c][num_q_heads][head_dim] / [S][c][num_q_heads]
+ * arrays medha_lse_merge takes.
+ *
+ *   q                dev  bf16 [num_tokens][num_q_heads][head_dim], 16-byte aligned
+ *   page_table       dev  int32, concatenated slices
+ *   page_table_offs  host int64 [items + 1]; slice i holds >= ceil(kv_len[i] / 16) entries
+ *   q_row            host int32 [items], q_row[i] + chunk_len[i] <= num_tokens
+ *   chunk_len        host int32 [items], >= 1
+ *   kv_len           host int32 [items], >= 0
+ *   visible0         host int32 [items], |visible0| <= 2^30
+ *   out_partial      dev  fp32 [sum chunk_len][num_q_heads][head_dim], 16-byte aligned
+ *   lse_partial      dev  fp32 [sum chunk_len][num_q_heads]
+ *   workspace        as above, size from medha_chunk_partial_workspace_bytes
+ */
+int medha_chunk_partial_attn(const void* q, int32_t num_tokens, const medha_kv_cache* kv,
+                             const int32_t* page_table, const int64_t* page_table_offs,
+                             const int32_t* q_row, const int32_t* chunk_len,
+                             const int32_t* kv_len, const int32_t* visible0, int32_t items,
+                             int32_t num_q_heads, float softmax_scale, float* out_partial,
+                             float* lse_partial, void* workspace, size_t workspace_bytes,
+                             void* hip_stream);
+
+size_t medha_chunk_partial_workspace_bytes(const int32_t* chunk_len, const int32_t* kv_len,
+                                           int32_t items, int32_t num_q_heads,
+                                           int32_t num_kv_heads, int32_t head_dim);
+
+/*
  * LSE merge (paper section 3.3: the partial outputs of the KV shards are
  * combined with the online-softmax identity).  For every (row, head):
  *     LSE = ln sum_s exp(LSE_s)        O = sum_s exp(LSE_s - LSE) * O_s

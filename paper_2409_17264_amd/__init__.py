@@ -8,6 +8,8 @@ from .binding import (  # noqa: F401
     MedhaError,
     ceiling_mfma_bf16,
     ceiling_stream_read,
+    chunk_partial_attn,
+    chunk_partial_workspace_bytes,
     chunked_prefill_attn,
     chunked_prefill_workspace_bytes,
     decode_partial_attn,

@@ -22,6 +22,8 @@ EXPORTS = (
     "medha_chunked_prefill_workspace_bytes",
     "medha_decode_partial_attn",
     "medha_decode_partial_workspace_bytes",
+    "medha_chunk_partial_attn",
+    "medha_chunk_partial_workspace_bytes",
     "medha_lse_merge",
     "medha_kv_append",
     "medha_describe_plan",
@@ -77,6 +79,11 @@ def load_library():
                                               i32, i32, f32, vp, vp, vp, sz, vp]
     lib.medha_decode_partial_workspace_bytes.restype = sz
     lib.medha_decode_partial_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
+    lib.medha_chunk_partial_attn.restype = ctypes.c_int
+    lib.medha_chunk_partial_attn.argtypes = [vp, i32, ctypes.POINTER(_KvCache), vp, vp, vp, vp, vp,
+                                             vp, i32, i32, f32, vp, vp, vp, sz, vp]
+    lib.medha_chunk_partial_workspace_bytes.restype = sz
+    lib.medha_chunk_partial_workspace_bytes.argtypes = [vp, vp, i32, i32, i32, i32]
     lib.medha_lse_merge.restype = ctypes.c_int
     lib.medha_lse_merge.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp]
     lib.medha_kv_append.restype = ctypes.c_int
@@ -234,6 +241,51 @@ def decode_partial_attn(q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Ten
         _dp(q), num_queries, ctypes.byref(kv), _dp(page_table), _hp(offs), _hp(qi), _hp(kl), items,
         h_q, float(softmax_scale), _dp(out_partial), _dp(lse_partial), _dp(workspace),
         workspace.numel(), _stream()))
+    return out_partial, lse_partial
+
+
+def chunk_partial_workspace_bytes(chunk_len, kv_len, num_q_heads: int, num_kv_heads: int,
+                                  head_dim: int) -> int:
+    chk, kl = _host(chunk_len, np.int32), _host(kv_len, np.int32)
+    return int(load_library().medha_chunk_partial_workspace_bytes(
+        _hp(chk), _hp(kl), len(chk), num_q_heads, num_kv_heads, head_dim))
+
+
+def chunk_partial_attn(q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor,
+                       page_table: torch.Tensor, page_table_offs, q_row, chunk_len, kv_len,
+                       visible0, softmax_scale: float,
+                       out_partial: Optional[torch.Tensor] = None,
+                       lse_partial: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None):
+    """Item i: rows q_row[i] .. +chunk_len[i] of q bf16 [tokens][h_q][d] against the kv_len[i]
+    keys of its page-table slice, row j seeing the first min(kv_len, max(0, visible0 + j)).
+    Returns (out_partial fp32 [sum chunk_len][h_q][d], lse_partial fp32 [sum chunk_len][h_q])."""
+    lib = load_library()
+    assert q.is_cuda and q.dtype == torch.bfloat16 and q.is_contiguous() and q.dim() == 3
+    assert page_table.is_cuda and page_table.dtype == torch.int32 and page_table.is_contiguous()
+    tokens, h_q, d = q.shape
+    kv = _kv(k_pool, v_pool)
+    offs = _host(page_table_offs, np.int64)
+    qr, chk = _host(q_row, np.int32), _host(chunk_len, np.int32)
+    kl, v0 = _host(kv_len, np.int32), _host(visible0, np.int32)
+    items = len(qr)
+    assert len(chk) == items and len(kl) == items and len(v0) == items and len(offs) == items + 1
+    assert int(offs[-1]) <= page_table.numel()
+    rows = int(chk.sum())
+    if out_partial is None:
+        out_partial = torch.empty((rows, h_q, d), dtype=torch.float32, device=q.device)
+    if lse_partial is None:
+        lse_partial = torch.empty((rows, h_q), dtype=torch.float32, device=q.device)
+    assert out_partial.dtype == torch.float32 and out_partial.is_contiguous()
+    assert lse_partial.dtype == torch.float32 and lse_partial.is_contiguous()
+    assert out_partial.shape == (rows, h_q, d) and lse_partial.shape == (rows, h_q)
+    if workspace is None:
+        workspace = _workspace(lib.medha_chunk_partial_workspace_bytes(
+            _hp(chk), _hp(kl), items, h_q, kv.num_kv_heads, d), q.device)
+    _check(lib.medha_chunk_partial_attn(
+        _dp(q), tokens, ctypes.byref(kv), _dp(page_table), _hp(offs), _hp(qr), _hp(chk), _hp(kl),
+        _hp(v0), items, h_q, float(softmax_scale), _dp(out_partial), _dp(lse_partial),
+        _dp(workspace), workspace.numel(), _stream()))
     return out_partial, lse_partial
 
 

@@ -27,10 +27,12 @@ constexpr float kRescaleSlack = 8.f;  // log2 units a row maximum may exceed the
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-// One sequence of a launch.  Query row j (0 <= j < chunk_len) attends to keys
-// [0, prefix_len + j] of the paged sequence whose page table starts at pt_off.
-// A decode item is chunk_len == 1 with prefix_len == kv_len - 1 (so -1 means
-// "no keys").  The sequence owns workgroup slots
+// One sequence of a launch.  Its page table (from pt_off) describes kv_len keys;
+// query row j (0 <= j < chunk_len) attends to keys [0, min(prefix_len + j, kv_len - 1)]
+// of them, to none if that is negative.  Chunked prefill: kv_len = prefix_len +
+// chunk_len.  A decode item: chunk_len == 1, prefix_len == kv_len - 1.  A chunk
+// against a KV shard: prefix_len + 1 = keys of the shard its first row sees, which
+// may be <= 0 or exceed kv_len.  The sequence owns workgroup slots
 // [work_start, work_start + 8 * ceil(h_kv * n_split * n_row_tiles / 8)).
 struct SeqDesc {
   int64_t pt_off;           // first entry of the sequence in the page table
@@ -44,8 +46,10 @@ struct SeqDesc {
   int32_t tiles_per_split;  // KV tiles per range
   int32_t part_row;         // first token row of this sequence in the partial workspace
   int32_t row_rank;         // rank of the sequence's first token row among the launch's rows
+  int32_t kv_len;           // keys the page-table slice describes
+  int32_t reserved;
 };
-static_assert(sizeof(SeqDesc) == 48, "SeqDesc layout");
+static_assert(sizeof(SeqDesc) == 56, "SeqDesc layout");
 
 // Kernel arguments of the attention kernels.  Up to kMaxInlineSeq descriptors
 // ride in the argument block itself (no host-to-device copy, no

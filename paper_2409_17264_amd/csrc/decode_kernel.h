@@ -97,7 +97,8 @@ decode_kernel(const AttnArgs args) {
   const int rr = valid ? col : (n_rows - 1);
   const int tok = rr / gqa;
   const int hq = kv_head * gqa + rr % gqa;
-  rb.limit = sd.prefix_len + tok;
+  const int kv_total = sd.kv_len;  // keys that exist
+  rb.limit = min(sd.prefix_len + tok, kv_total - 1);
   {
     const unsigned flip = args.scale_log2 < 0.f ? 0x80008000u : 0u;
     const __bf16* qp = args.q + ((int64_t)(sd.q_row + tok) * args.h_q + hq) * D + half * 8;
@@ -111,11 +112,11 @@ decode_kernel(const AttnArgs args) {
   }
 
   // This workgroup's key range and its 32-key blocks.
-  const int kv_total = sd.prefix_len + sd.chunk_len;  // keys that exist (and the last row sees)
+  const int keys_needed = max(0, min(kv_total, sd.prefix_len + sd.chunk_len));  // last row's
   const int k_begin = split * sd.tiles_per_split * G::kSplitKeys;
-  const int k_end = min(kv_total, k_begin + sd.tiles_per_split * G::kSplitKeys);
+  const int k_end = min(keys_needed, k_begin + sd.tiles_per_split * G::kSplitKeys);
   const int n_blocks = k_end > k_begin ? (k_end - k_begin + G::kBlockKeys - 1) / G::kBlockKeys : 0;
-  const int unmasked_keys = sd.prefix_len + 1;  // visible to every row
+  const int unmasked_keys = max(0, min(kv_total, sd.prefix_len + 1));  // visible to every row
   const int last_page = (kv_total - 1) >> 4;
   ConstI32Ptr pt = (ConstI32Ptr)(args.page_table + sd.pt_off);
 

@@ -251,6 +251,66 @@ int medha_decode_partial_attn(const void* q, int32_t num_queries, const medha_kv
                   workspace, workspace_bytes, hip_stream);
 }
 
+size_t medha_chunk_partial_workspace_bytes(const int32_t* chunk_len, const int32_t* kv_len,
+                                          int32_t items, int32_t num_q_heads,
+                                          int32_t num_kv_heads, int32_t head_dim) {
+  if (items < 0 || (items > 0 && (chunk_len == nullptr || kv_len == nullptr))) return 0;
+  if (check_heads(num_q_heads, num_kv_heads, head_dim, kPageSize) != MEDHA_OK) return 0;
+  std::vector<SeqInput> seqs(items);
+  int64_t row = 0;
+  for (int i = 0; i < items; ++i) {
+    if (chunk_len[i] < 1 || kv_len[i] < 0) return 0;
+    // the plan depends on the row count and the key count only
+    seqs[i] = SeqInput{0, 0, (int32_t)row, chunk_len[i], kv_len[i] - 1, kv_len[i]};
+    row += chunk_len[i];
+    if (row > INT32_MAX) return 0;
+  }
+  return make_plan(seqs.data(), items, num_q_heads, num_kv_heads, head_dim, current_num_cus())
+      .bytes;
+}
+
+int medha_chunk_partial_attn(const void* q, int32_t num_tokens, const medha_kv_cache* kv,
+                             const int32_t* page_table, const int64_t* page_table_offs,
+                             const int32_t* q_row, const int32_t* chunk_len,
+                             const int32_t* kv_len, const int32_t* visible0, int32_t items,
+                             int32_t num_q_heads, float softmax_scale, float* out_partial,
+                             float* lse_partial, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+  if (items < 0 || num_tokens < 0) return MEDHA_ERR_INVALID_ARG;
+  int rc = check_kv(kv, num_q_heads);
+  if (rc != MEDHA_OK) return rc;
+  if (items == 0) return MEDHA_OK;
+  if (q == nullptr || page_table == nullptr || page_table_offs == nullptr || q_row == nullptr ||
+      chunk_len == nullptr || kv_len == nullptr || visible0 == nullptr ||
+      out_partial == nullptr || lse_partial == nullptr)
+    return MEDHA_ERR_INVALID_ARG;
+  if (!aligned(q, 16) || !aligned(out_partial, 16) || !aligned(lse_partial, 4) ||
+      !std::isfinite(softmax_scale))
+    return MEDHA_ERR_INVALID_ARG;
+  constexpr int32_t kMaxVisible = 1 << 30;
+  std::vector<SeqInput> seqs(items);
+  int64_t row = 0;
+  for (int i = 0; i < items; ++i) {
+    if (chunk_len[i] < 1 || kv_len[i] < 0 || q_row[i] < 0 ||
+        (int64_t)q_row[i] + chunk_len[i] > num_tokens)
+      return MEDHA_ERR_INVALID_ARG;
+    if (visible0[i] < -kMaxVisible || visible0[i] > kMaxVisible || chunk_len[i] > kMaxVisible)
+      return MEDHA_ERR_INVALID_ARG;
+    const int64_t have = page_table_offs[i + 1] - page_table_offs[i];
+    if (page_table_offs[i] < 0 || have < ceil_div(kv_len[i], kPageSize))
+      return MEDHA_ERR_INVALID_ARG;
+    // row j sees keys [0, visible0 + j): its last visible key is (visible0 - 1) + j
+    seqs[i] = SeqInput{page_table_offs[i], q_row[i], (int32_t)row, chunk_len[i], visible0[i] - 1,
+                       kv_len[i]};
+    row += chunk_len[i];
+    if (row > INT32_MAX) return MEDHA_ERR_INVALID_ARG;
+  }
+  const Plan plan = make_plan(seqs.data(), items, num_q_heads, kv->num_kv_heads, kv->head_dim,
+                              current_num_cus());
+  return run_plan(plan, q, kv, page_table, num_q_heads, softmax_scale, out_partial, lse_partial,
+                  workspace, workspace_bytes, hip_stream);
+}
+
 int medha_describe_plan(const int32_t* prefix_len, const int32_t* chunk_len, int32_t batch,
                         int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim,
                         int32_t num_cus, medha_plan_entry* entries, int32_t* grid_rows,

@@ -37,6 +37,7 @@ struct Plan {
 struct SeqInput {
   int64_t pt_off;
   int32_t q_row, out_row, chunk_len, prefix_len;
+  int32_t kv_len = -1;  // keys in the page-table slice; -1: prefix_len + chunk_len
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -51,15 +52,14 @@ inline void plan_launch(LaunchPlan& lp, int h_kv, int gqa, int target_wgs, int m
   int64_t unsplit_wgs = 0, total_steps = 0;
   for (SeqDesc& sd : lp.descs) {
     sd.n_row_tiles = (int)ceil_div((int64_t)sd.chunk_len * gqa, sh.rows_per_wg);
-    const int64_t kv_tiles = ceil_div((int64_t)sd.prefix_len + sd.chunk_len, sh.tile_keys);
+    const int64_t kv_tiles = ceil_div((int64_t)sd.kv_len, sh.tile_keys);
     unsplit_wgs += (int64_t)h_kv * sd.n_row_tiles;
     total_steps += (int64_t)h_kv * sd.n_row_tiles * kv_tiles;
   }
   const int64_t steps_target = std::max<int64_t>(1, ceil_div(total_steps, target_wgs));
   int slot = 0, rank = 0;
   for (SeqDesc& sd : lp.descs) {
-    const int64_t kv_tiles =
-        std::max<int64_t>(1, ceil_div((int64_t)sd.prefix_len + sd.chunk_len, sh.tile_keys));
+    const int64_t kv_tiles = std::max<int64_t>(1, ceil_div((int64_t)sd.kv_len, sh.tile_keys));
     int64_t n_split = 1;
     if (unsplit_wgs < target_wgs) {
       n_split = ceil_div(kv_tiles, steps_target);
@@ -98,6 +98,7 @@ inline Plan make_plan(const SeqInput* seqs, int batch, int h_q, int h_kv, int he
     sd.out_row = seqs[b].out_row;
     sd.chunk_len = seqs[b].chunk_len;
     sd.prefix_len = seqs[b].prefix_len;
+    sd.kv_len = seqs[b].kv_len >= 0 ? seqs[b].kv_len : sd.prefix_len + sd.chunk_len;
     const int64_t n_rows = (int64_t)sd.chunk_len * gqa;
     LaunchPlan& lp = n_rows <= 32 ? plan.keys : plan.rows;
     lp.descs.push_back(sd);

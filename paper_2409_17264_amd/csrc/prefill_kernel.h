@@ -515,6 +515,8 @@ __device__ __forceinline__ SeqDesc uniform(const SeqDesc& d) {
   u.tiles_per_split = __builtin_amdgcn_readfirstlane(d.tiles_per_split);
   u.part_row = __builtin_amdgcn_readfirstlane(d.part_row);
   u.row_rank = __builtin_amdgcn_readfirstlane(d.row_rank);
+  u.kv_len = __builtin_amdgcn_readfirstlane(d.kv_len);
+  u.reserved = 0;
   return u;
 }
 
@@ -642,7 +644,8 @@ __global__ void __launch_bounds__(512) prefill_kernel(const AttnArgs args) {
   const int rr = valid ? r : (n_rows - 1);
   const int tok = rr / gqa;
   const int hq = kv_head * gqa + rr % gqa;
-  rb.limit = sd.prefix_len + tok;
+  const int kv_total = sd.kv_len;  // keys that exist
+  rb.limit = min(sd.prefix_len + tok, kv_total - 1);
   {
     // a negative scale is folded into the sign of Q (exact), so the kernel's scale is >= 0
     const unsigned flip = args.scale_log2 < 0.f ? 0x80008000u : 0u;
@@ -658,13 +661,13 @@ __global__ void __launch_bounds__(512) prefill_kernel(const AttnArgs args) {
 
   // Keys this row tile needs: up to the limit of its last row.
   const int last_row = min(n_rows, wg_row0 + Shape::kRowsPerWg) - 1;
-  const int keys_needed = sd.prefix_len + last_row / gqa + 1;
-  const int kv_total = sd.prefix_len + sd.chunk_len;
+  const int keys_needed = max(0, min(kv_total, sd.prefix_len + last_row / gqa + 1));
   const int tiles_needed = (keys_needed + 63) / 64;
   const int kt_begin = split * sd.tiles_per_split;
   const int kt_end = min(tiles_needed, kt_begin + sd.tiles_per_split);
   // tiles below kt_mid are fully visible to every row of the workgroup
-  const int unmasked_keys = sd.prefix_len + min(wg_row0, n_rows - 1) / gqa + 1;
+  const int unmasked_keys =
+      max(0, min(kv_total, sd.prefix_len + min(wg_row0, n_rows - 1) / gqa + 1));
   const int kt_mid = max(kt_begin, min(kt_end, unmasked_keys / 64));
 
   ConstI32Ptr pt = (ConstI32Ptr)(args.page_table + sd.pt_off);

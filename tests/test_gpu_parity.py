@@ -328,3 +328,81 @@ def test_chunk_by_chunk_prefill_on_the_gpu_equals_one_shot_oracle():
     assert start == n
     torch.cuda.synchronize()
     check(torch.cat(outs).cpu().numpy(), torch.cat(lses).cpu().numpy(), ro, rl, "chunk-by-chunk")
+
+
+# ------------------------------------- KV-cache-parallel partials of a prefill chunk
+def _oracle_chunk_partial(b, pt, pto, q_row, chunk_len, kv_len, vis0):
+    return oracle.chunk_partial_attn(wl.bf16_bits(b.q), wl.bf16_bits(b.k_pool),
+                                     wl.bf16_bits(b.v_pool), pt, pto, q_row, chunk_len, kv_len,
+                                     vis0, b.scale)
+
+
+@pytest.mark.parametrize("h_q,h_kv,d", [(8, 2, 128), (4, 4, 64), (32, 8, 128)])
+def test_chunk_partial_items_match_oracle(h_q, h_kv, d):
+    """Items of every kind in one call: unmasked shards, causal shards, rows that see nothing,
+    an empty shard, ragged lengths, chunks small enough for the key-split kernel."""
+    n = 900
+    b = wl.make_prefill_batch("cp", h_q, h_kv, d, [n - 200], [200], seed=h_q + d,
+                              poison_unused=True)
+    #        q_row chunk kv_len visible0   slice (first page, of the one sequence)
+    items = [(0, 200, 700, 700, 0),      # shard before the chunk: everything visible
+             (0, 200, 900, 701, 0),      # the whole sequence, causal: plain chunked prefill
+             (0, 200, 132, -67, 48),     # shard starting at key 768: early rows see nothing
+             (10, 150, 0, 5, 0),         # empty shard
+             (0, 3, 333, 2000, 16),      # tiny chunk (key-split kernel), no mask
+             (197, 3, 100, 98, 0),       # tiny chunk, causal tail
+             (5, 64, 77, 30, 32),        # ragged, mask starts inside the first tile
+             (0, 200, 64, 64, 0)]        # exactly one tile
+    if h_q // h_kv > 8:
+        pytest.skip("group size")
+    q_row, chunk, kv_len, vis0, first = (np.array(x, np.int32) for x in zip(*items))
+    slices = [b.page_table[f:f + (kl + 15) // 16] for f, kl in zip(first, kv_len)]
+    pt = np.concatenate(slices)
+    pto = np.concatenate([[0], np.cumsum([len(s) for s in slices])]).astype(np.int64)
+    ro, rl = _oracle_chunk_partial(b, pt, pto, q_row, chunk, kv_len, vis0)
+    b = to_dev(b)
+    o, l = medha.chunk_partial_attn(b.q, b.k_pool, b.v_pool, torch.from_numpy(pt).cuda(), pto,
+                                    q_row, chunk, kv_len, vis0, b.scale)
+    torch.cuda.synchronize()
+    check(o.cpu().numpy(), l.cpu().numpy(), ro, rl, f"chunk partial hq{h_q} d{d}")
+
+
+@pytest.mark.parametrize("prefix,chunk,shards", [(4096, 512, 4), (1000, 300, 3), (0, 700, 2),
+                                                 (8192, 8, 8)])
+def test_chunk_kvp_shards_merge_to_unsplit_attention(prefix, chunk, shards):
+    """A chunk against page-aligned KV shards (only the last ones causal), merged with the LSE
+    merge, against the oracle's plain chunked prefill and the library's own unsplit call."""
+    h_q, h_kv, d = 8, 2, 128
+    b = wl.make_prefill_batch("kvp", h_q, h_kv, d, [prefix], [chunk], seed=prefix + shards)
+    ro, rl = oracle_prefill(b)
+    n = prefix + chunk
+    per = ((n + shards - 1) // shards + 15) // 16 * 16
+    cuts = [min(n, i * per) for i in range(shards + 1)]
+    slices = [b.page_table[lo // 16:(hi + 15) // 16] for lo, hi in zip(cuts[:-1], cuts[1:])]
+    pt = np.concatenate(slices)
+    pto = np.concatenate([[0], np.cumsum([len(s) for s in slices])]).astype(np.int64)
+    kv_len = np.diff(cuts).astype(np.int32)
+    vis0 = np.array([prefix + 1 - lo for lo in cuts[:-1]], np.int32)
+    b = to_dev(b)
+    po, pl = medha.chunk_partial_attn(b.q, b.k_pool, b.v_pool, torch.from_numpy(pt).cuda(), pto,
+                                      np.zeros(shards, np.int32), np.full(shards, chunk, np.int32),
+                                      kv_len, vis0, b.scale)
+    o, l = medha.lse_merge(po.view(shards, chunk, h_q, d), pl.view(shards, chunk, h_q))
+    torch.cuda.synchronize()
+    check(o.cpu().numpy(), l.cpu().numpy(), ro, rl, f"chunk KVP P{prefix} c{chunk} S{shards}")
+    uo, ul = gpu_prefill(b)
+    assert np.max(np.abs(o.cpu().numpy() - uo)) < 2e-3
+    assert np.max(np.abs(l.cpu().numpy() - ul)) < 1e-4
+
+
+def test_chunk_partial_rejects_bad_arguments():
+    b = to_dev(wl.make_prefill_batch("bad", 8, 2, 128, [100], [20], seed=1))
+    pt = torch.from_numpy(b.page_table).cuda()
+    args = dict(q_row=[0], chunk_len=[20], kv_len=[120], visible0=[101])
+    for key, bad in (("q_row", [1]), ("chunk_len", [0]), ("kv_len", [-1]), ("kv_len", [1000]),
+                     ("visible0", [(1 << 30) + 1])):
+        a = dict(args)
+        a[key] = bad
+        with pytest.raises(medha.MedhaError):
+            medha.chunk_partial_attn(b.q, b.k_pool, b.v_pool, pt, b.page_table_offs, a["q_row"],
+                                     a["chunk_len"], a["kv_len"], a["visible0"], b.scale)
