@@ -12,7 +12,9 @@ The same JSON line also carries, each measured in its own timed loop:
            of 262,144 through the decode-partial entry point, then the LSE
            merge): KV-read GB/s against the HBM roofline;
   sweep    the Llama-3-70B tensor-parallel share (8 q / 1 kv head, 1M prefix)
-           at chunk sizes 512..8192: TFLOP/s per chunk size;
+           at chunk sizes 512..8192: TFLOP/s per chunk size; and, for chunk 2048,
+           one GPU's share under KV-cache parallelism of degree 1, 2, 4, 8 (the
+           chunk against one KV shard) plus the merge of the partials;
   append   the chunk's K/V scattered into the paged pools (the step before the
            attention call): microseconds and GB/s;
   mixed    one 1024-token prefill chunk at a 524,288-token prefix plus 64
@@ -295,7 +297,42 @@ def main():
                           "frac_of_peak": tf / PEAK_BF16_TFLOPS})
         result["sweep"] = {"workload": "cfg4 Llama-3-70B TP8 share: 8 q / 1 kv head, d 128, "
                                        "prefix 1,048,576", "points": sweep}
-        del base, bb, run
+        del bb, run
+        # KV-cache parallelism for the chunk: what ONE GPU of a KVP group of S does -- the
+        # chunk against its shard of the 1M-token cache (here the last, causal shard) -- and
+        # the merge of S partials.  One GPU, so the S shards are not run concurrently.
+        chunk = 2048
+        n = int(base.prefix_len[0]) + chunk
+        pt_dev = torch.from_numpy(base.page_table).cuda()
+        qc = base.q[:chunk].contiguous()
+        kvp = []
+        for shards in (1, 2, 4, 8):
+            per = ((n + shards - 1) // shards + 15) // 16 * 16
+            lo = (shards - 1) * per
+            offs = np.array([lo // 16, lo // 16 + (n - lo + 15) // 16], np.int64)
+            po = torch.empty((chunk, base.h_q, base.d), dtype=torch.float32, device="cuda")
+            pl = torch.empty((chunk, base.h_q), dtype=torch.float32, device="cuda")
+            ws = torch.empty(max(256, medha.chunk_partial_workspace_bytes(
+                [chunk], [n - lo], base.h_q, base.h_kv, base.d)), dtype=torch.uint8, device="cuda")
+            t = time_calls(lambda: medha.chunk_partial_attn(
+                qc, base.k_pool, base.v_pool, pt_dev, offs, [0], [chunk], [n - lo],
+                [int(base.prefix_len[0]) + 1 - lo], base.scale, po, pl, ws),
+                max(3, args.steps // 3), 2)
+            allo = torch.empty((shards, chunk, base.h_q, base.d), dtype=torch.float32, device="cuda")
+            alll = torch.zeros((shards, chunk, base.h_q), dtype=torch.float32, device="cuda")
+            mo = torch.empty((chunk, base.h_q, base.d), dtype=torch.float32, device="cuda")
+            ml = torch.empty((chunk, base.h_q), dtype=torch.float32, device="cuda")
+            tm = time_calls(lambda: medha.lse_merge(allo, alll, mo, ml), 10, 3)
+            log(f"kvp chunk {chunk} / {shards} shards: shard {t['event_ms_mean']:.3f} ms, "
+                f"merge {tm['event_ms_mean'] * 1e3:.1f} us")
+            kvp.append({"shards": shards, "shard_keys": n - lo, "shard_ms": t["event_ms_mean"],
+                        "merge_us": tm["event_ms_mean"] * 1e3})
+            del po, pl, ws, allo, alll, mo, ml
+        result["kvp_prefill"] = {
+            "workload": "cfg4 shape, chunk 2048 at prefix 1,048,576: the chunk against the last of "
+                        "S page-aligned KV shards (one GPU's share under KVP degree S) and the "
+                        "LSE merge of S partials", "points": kvp}
+        del base, pt_dev, qc
         torch.cuda.empty_cache()
 
     # ---------------------------------------------------------------- mixed
