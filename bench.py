@@ -15,6 +15,9 @@ The same JSON line also carries, each measured in its own timed loop:
            at chunk sizes 512..8192: TFLOP/s per chunk size; and, for chunk 2048,
            one GPU's share under KV-cache parallelism of degree 1, 2, 4, 8 (the
            chunk against one KV shard) plus the merge of the partials;
+  policy   (with sweep) the paper's chunk-size policy on this device's timings:
+           runtime model fitted to the sweep, chunk sizes for a 20 ms iteration,
+           prefill-time cache, microseconds per decision;
   append   the chunk's K/V scattered into the paged pools (the step before the
            attention call): microseconds and GB/s;
   mixed    one 1024-token prefill chunk at a 524,288-token prefix plus 64
@@ -26,7 +29,7 @@ and `cpu_baseline`: the fp64 CPU oracle timed on a bounded sample of rows of
 the headline workload on this machine's host cores (a reported baseline only).
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W]
-                [--sections ceilings,main,append,decode,sweep,mixed,cpu[,copy]]
+                [--sections ceilings,main,append,decode,sweep,policy,mixed,cpu[,copy]]
 """
 import argparse
 import json
@@ -137,7 +140,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--sections", default="ceilings,main,append,decode,sweep,mixed,cpu")
+    ap.add_argument("--sections", default="ceilings,main,append,decode,sweep,policy,mixed,cpu")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (KV-cache parallelism is exercised "
@@ -328,6 +331,51 @@ def main():
             kvp.append({"shards": shards, "shard_keys": n - lo, "shard_ms": t["event_ms_mean"],
                         "merge_us": tm["event_ms_mean"] * 1e3})
             del po, pl, ws, allo, alll, mo, ml
+        if "policy" in sections:
+            # the scheduling helpers on THIS device's timings: fit the runtime model to the sweep
+            # plus a few shorter prefixes, then ask the paper's policy what it would do
+            from paper_2409_17264_amd import policy as pol
+            samples = [(int(base.prefix_len[0]), p["chunk"], p["ms"] * 1e-3) for p in sweep]
+            for prefix, chunk2 in ((131072, 1024), (131072, 4096), (524288, 1024), (524288, 4096)):
+                bb2 = wl.PrefillBatch(f"cfg4_p{prefix}_c{chunk2}", base.h_q, base.h_kv, base.d,
+                                      np.array([prefix], np.int32), np.array([chunk2], np.int32),
+                                      base.page_table, base.page_table_offs, base.num_pages,
+                                      base.q[:chunk2].contiguous(), base.k_pool, base.v_pool,
+                                      base.scale)
+                run2, _, _ = prefill_runner(bb2)
+                t2 = time_calls(run2, max(3, args.steps // 3), 2)
+                samples.append((prefix, chunk2, t2["event_ms_mean"] * 1e-3))
+                del bb2, run2
+            model, fit_err = pol.fit_time_model([x[0] for x in samples], [x[1] for x in samples],
+                                                [x[2] for x in samples])
+            t_target = 0.020
+            picks = {str(kv): pol.get_chunk_size(model, kv, 1 << 30, True, False, 0.0, 0.4, 0.0,
+                                                 t_target, 16384)
+                     for kv in (0, 65536, 262144, 1048576)}
+            t0 = time.perf_counter()
+            cache = pol.build_prefill_cache(model, 1 << 20, 1024, t_target, 16384)
+            t_cache = time.perf_counter() - t0
+            t0 = time.perf_counter()
+            for i in range(20000):
+                pol.get_chunk_size(model, 1000 * (i % 1000), 1 << 30, True, False, 0.1, 0.4, 1e-3,
+                                   t_target, 16384)
+            t_call = (time.perf_counter() - t0) / 20000
+            log(f"policy: fit over {len(samples)} timings: t_fixed {model.t_fixed * 1e6:.1f} us, "
+                f"t_token {model.t_token * 1e9:.2f} ns, t_pair {model.t_pair * 1e12:.4f} ps, "
+                f"max rel err {fit_err * 100:.1f} %; chunk for a 20 ms iteration by cache size "
+                f"{picks}; est. attention time of a 1M-token prefill {cache[-1]:.2f} s; "
+                f"{t_call * 1e6:.2f} us per chunk-size decision, cache of 1025 entries in "
+                f"{t_cache * 1e3:.1f} ms")
+            result["policy"] = {
+                "workload": "cfg4 shape (one layer's attention, one TP share): runtime model fitted "
+                            "to this run's timings, Algorithm 2 chunk sizes for a 20 ms iteration, "
+                            "Algorithm 3 prefill-time cache to 1M tokens at 1K granularity",
+                "samples": [{"kv": a, "chunk": b, "s": c} for a, b, c in samples],
+                "model": {"t_fixed": model.t_fixed, "t_token": model.t_token,
+                          "t_pair": model.t_pair},
+                "fit_max_rel_err": fit_err, "chunk_for_20ms_by_kv": picks,
+                "est_prefill_attention_s_1m": float(cache[-1]),
+                "us_per_decision": t_call * 1e6, "cache_build_ms": t_cache * 1e3}
         result["kvp_prefill"] = {
             "workload": "cfg4 shape, chunk 2048 at prefix 1,048,576: the chunk against the last of "
                         "S page-aligned KV shards (one GPU's share under KVP degree S) and the "

@@ -14,6 +14,7 @@
 #include "decode_kernel.h"
 #include "merge_kernel.h"
 #include "planner.h"
+#include "policy.h"
 #include "prefill_kernel.h"
 
 namespace medha {
@@ -463,6 +464,196 @@ int medha_ceiling_stream_read(const void* src, size_t bytes, int32_t blocks, voi
                      static_cast<hipStream_t>(hip_stream), static_cast<const u32x4*>(src),
                      bytes / 16, static_cast<u32x4*>(sink));
   return hipGetLastError() == hipSuccess ? MEDHA_OK : MEDHA_ERR_HIP;
+}
+
+// ------------------------------------------------------------------ policy (host only)
+double medha_policy_chunk_time(const medha_time_model* model, int64_t kv_size, int64_t chunk) {
+  if (!policy::valid(model) || kv_size < 0 || chunk < 0)
+    return std::numeric_limits<double>::quiet_NaN();
+  return policy::chunk_time(*model, kv_size, chunk);
+}
+
+int medha_policy_fit_time_model(const int64_t* kv_size, const int64_t* chunk,
+                                const double* seconds, int32_t n, medha_time_model* model,
+                                double* max_rel_err) {
+  if (kv_size == nullptr || chunk == nullptr || seconds == nullptr || model == nullptr || n < 3)
+    return -1;
+  std::vector<double> x[3];
+  for (int i = 0; i < n; ++i) {
+    if (kv_size[i] < 0 || chunk[i] < 1 || !(seconds[i] > 0.0) || !std::isfinite(seconds[i]))
+      return -1;
+    x[0].push_back(1.0);
+    x[1].push_back((double)chunk[i]);
+    x[2].push_back((double)(chunk[i] * kv_size[i]) + (double)(chunk[i] * (chunk[i] + 1)) / 2.0);
+  }
+  // all three columns first; drop a column whose coefficient comes out negative and refit
+  bool use[3] = {true, true, true};
+  double coef[3] = {0, 0, 0};
+  for (int round = 0; round < 3; ++round) {
+    int cols[3], k = 0;
+    for (int j = 0; j < 3; ++j)
+      if (use[j]) cols[k++] = j;
+    if (k == 0 || !policy::fit_columns(x, seconds, n, cols, k, coef)) return -1;
+    int worst = -1;
+    for (int j = 0; j < 3; ++j)
+      if (use[j] && coef[j] < 0.0 && (worst < 0 || coef[j] < coef[worst])) worst = j;
+    if (worst < 0) break;
+    use[worst] = false;
+    coef[worst] = 0.0;
+  }
+  for (double c : coef)
+    if (!std::isfinite(c) || c < 0.0) return -1;
+  *model = medha_time_model{coef[0], coef[1], coef[2], 0.0, 0.0};
+  if (max_rel_err) {
+    double worst = 0.0;
+    for (int i = 0; i < n; ++i) {
+      const double pred = model->t_fixed + policy::chunk_time(*model, kv_size[i], chunk[i]);
+      worst = std::max(worst, std::fabs(pred - seconds[i]) / seconds[i]);
+    }
+    *max_rel_err = worst;
+  }
+  return 0;
+}
+
+int64_t medha_policy_max_chunk(const medha_time_model* model, int64_t kv_size, double t_budget,
+                               int64_t max_chunk) {
+  if (!policy::valid(model) || kv_size < 0 || max_chunk < 0 || std::isnan(t_budget)) return -1;
+  if (kv_size > (1ll << 40) || max_chunk > (1 << 24)) return -1;  // products stay exact in fp64
+  return policy::max_chunk(*model, kv_size, t_budget, max_chunk);
+}
+
+int64_t medha_policy_get_chunk_size(const medha_time_model* model, int64_t kv_size,
+                                    int64_t remaining, int32_t is_long, int32_t batch_has_long,
+                                    double rel_slack, double rho_max, double t_current,
+                                    double t_target, int64_t max_chunk) {
+  if (!policy::valid(model) || kv_size < 0 || remaining < 0 || max_chunk < 0) return -1;
+  if (kv_size > (1ll << 40) || max_chunk > (1 << 24)) return -1;
+  if (std::isnan(rel_slack) || !(rho_max >= 0.0 && rho_max <= 1.0) || std::isnan(t_current) ||
+      !(t_target >= 0.0))
+    return -1;
+  if (is_long && batch_has_long) return 0;
+  const double rho = std::min(rho_max, std::max(0.0, rel_slack));
+  const double t_effective = t_target * (1.0 - rho);
+  const double t_budget = t_effective - t_current;
+  if (t_budget <= 0.0) return 0;
+  return policy::max_chunk(*model, kv_size, t_budget, std::min(max_chunk, remaining));
+}
+
+double medha_policy_simulate_prefill(const medha_time_model* model, int64_t length,
+                                     double t_target, int64_t max_chunk) {
+  if (!policy::valid(model) || length < 0 || max_chunk < 1 || max_chunk > (1 << 24) ||
+      length > (1ll << 40) || std::isnan(t_target))
+    return std::numeric_limits<double>::quiet_NaN();
+  return policy::simulate_prefill(*model, length, t_target, max_chunk);
+}
+
+int medha_policy_build_prefill_cache(const medha_time_model* model, int64_t l_max, int64_t delta,
+                                     double t_target, int64_t max_chunk, double* cache,
+                                     int64_t cache_len) {
+  if (!policy::valid(model) || cache == nullptr || delta < 1 || l_max < 0 ||
+      cache_len != l_max / delta + 1 || max_chunk < 1 || max_chunk > (1 << 24) ||
+      l_max > (1ll << 40) || std::isnan(t_target))
+    return -1;
+  // One walk over the chunks of the longest prefill.  The chunks of a shorter length are the
+  // same until the one that reaches its end, which is cut there: so every entry whose length
+  // falls inside the current chunk is (time before the chunk) + (the cut chunk), and an entry
+  // the walk never reaches (no chunk fits any more) keeps the time reached.
+  const medha_time_model& m = *model;
+  const double budget = t_target - m.t_fixed;
+  double total = 0.0;
+  int64_t done = 0, next = 0;  // next cache entry to fill
+  while (next < cache_len) {
+    const int64_t target = next * delta;
+    if (target <= done) {  // only for target == done: a length that ends on a chunk boundary
+      cache[next++] = total;
+      continue;
+    }
+    // the chunk a prefill of exactly `target` tokens would take at `done`
+    const int64_t c_here = policy::max_chunk(m, done, budget, std::min(max_chunk, target - done));
+    if (c_here == 0) {  // stuck: this and every longer length stop here
+      cache[next++] = total;
+      continue;
+    }
+    if (done + c_here == target) {
+      // the cut chunk ends the shorter prefill; the longest one may take a longer chunk here
+      cache[next++] = total + (m.t_fixed + policy::chunk_time(m, done, c_here));
+      continue;
+    }
+    // target lies beyond this chunk: c_here is the uncut chunk, the walk advances
+    total += m.t_fixed + policy::chunk_time(m, done, c_here);
+    done += c_here;
+  }
+  return 0;
+}
+
+double medha_policy_remaining_time(const double* cache, int64_t cache_len, int64_t delta,
+                                   int64_t l_total, int64_t l_processed) {
+  if (cache == nullptr || cache_len < 1 || delta < 1 || l_total < 0 || l_processed < 0)
+    return std::numeric_limits<double>::quiet_NaN();
+  auto lookup = [&](int64_t length) {
+    const int64_t i = length / delta, r = length % delta;
+    if (i >= cache_len - 1) return cache[cache_len - 1];
+    return cache[i] + (cache[i + 1] - cache[i]) * ((double)r / (double)delta);
+  };
+  return lookup(l_total) - lookup(l_processed);
+}
+
+double medha_policy_relative_slack(double arrival, double deadline, double now,
+                                   double remaining_work, double total_work) {
+  return (arrival + deadline - now - remaining_work) / total_work;
+}
+
+int medha_policy_simulate_schedule(int32_t policy_id, const double* arrival, const double* work,
+                                   const double* deadline, int32_t n, double quantum,
+                                   double* finish, double* first_start) {
+  if (arrival == nullptr || work == nullptr || deadline == nullptr || finish == nullptr ||
+      n < 1 || !(quantum > 0.0) || policy_id < 0 || policy_id > 2)
+    return -1;
+  for (int i = 0; i < n; ++i)
+    if (!(work[i] > 0.0) || !std::isfinite(work[i]) || !std::isfinite(arrival[i]) ||
+        arrival[i] < 0.0 || !std::isfinite(deadline[i]))
+      return -1;
+  constexpr double kEps = 1e-12;
+  std::vector<double> left(work, work + n);
+  std::vector<char> done(n, 0), started(n, 0);
+  int n_done = 0, current = -1;
+  double t = 0.0;
+  while (n_done < n) {
+    // requests that have arrived and are not finished
+    int pick = -1;
+    double best = 0.0;
+    bool any_ready = false;
+    double next_arrival = std::numeric_limits<double>::infinity();
+    for (int i = 0; i < n; ++i) {
+      if (done[i]) continue;
+      if (arrival[i] <= t + kEps) {
+        any_ready = true;
+        double key;
+        if (policy_id == 0) key = arrival[i];
+        else if (policy_id == 1) key = arrival[i] + deadline[i];
+        else key = (arrival[i] + deadline[i] - t - left[i]) / work[i];
+        if (pick < 0 || key < best) { pick = i; best = key; }
+      } else {
+        next_arrival = std::min(next_arrival, arrival[i]);
+      }
+    }
+    if (!any_ready) { t = next_arrival; continue; }
+    if (policy_id == 0 && current >= 0 && !done[current]) pick = current;  // no preemption
+    current = pick;
+    if (!started[current]) {
+      started[current] = 1;
+      if (first_start) first_start[current] = t;
+    }
+    const double run = std::min(quantum, left[current]);
+    left[current] -= run;
+    t += run;
+    if (left[current] <= kEps) {
+      done[current] = 1;
+      finish[current] = t;
+      ++n_done;
+    }
+  }
+  return 0;
 }
 
 }  // extern "C"

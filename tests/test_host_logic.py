@@ -7,16 +7,19 @@ import numpy as np
 import pytest
 
 import paper_2409_17264_amd as medha
-from paper_2409_17264_amd import binding
+from paper_2409_17264_amd import binding, policy
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "medha.h")).read()
-    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)          # drop comments
-    declared = set(re.findall(r"\b(medha_[a-z0-9_]+)\s*\(", body))
-    assert declared == set(binding.EXPORTS), declared ^ set(binding.EXPORTS)
+    declared = set()
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        header = open(os.path.join(ROOT, "include", name)).read()
+        body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)      # drop comments
+        declared |= set(re.findall(r"\b(medha_[a-z0-9_]+)\s*\(", body))
+    bound = set(binding.EXPORTS) | set(policy.EXPORTS)
+    assert declared == bound, declared ^ bound
     lib = medha.load_library()
     for name in declared:
         assert getattr(lib, name) is not None
