@@ -38,8 +38,9 @@ typedef struct medha_time_model {
  * negative sizes. */
 double medha_policy_chunk_time(const medha_time_model* model, int64_t kv_size, int64_t chunk);
 
-/* Least-squares fit of (t_fixed, t_token, t_pair) to n >= 3 measured
- * (kv_size, chunk, seconds) samples; t_decode and t_decode_key are set to 0.
+/* Least-squares fit, in relative error (sum of ((predicted - measured) / measured)^2),
+ * of (t_fixed, t_token, t_pair) to n >= 3 measured (kv_size, chunk, seconds)
+ * samples; t_decode and t_decode_key are set to 0.
  * A coefficient that comes out negative is clamped to 0 and the others refitted.
  * max_rel_err (optional) receives max |predicted - measured| / measured.
  * Returns 0, or -1 for bad arguments / a singular system. */

@@ -74,8 +74,10 @@ inline bool solve(double a[3][3], double b[3], int k) {
   return true;
 }
 
-// Least squares over the columns listed in `cols` (0: constant, 1: tokens, 2: pairs), with
-// each column scaled to unit maximum so that the normal equations stay well conditioned.
+// Least squares in RELATIVE error -- minimises sum ((prediction - y) / y)^2, i.e. every row
+// is weighted by 1 / y, so that a 0.5 ms sample counts like a 30 ms one -- over the columns
+// listed in `cols` (0: constant, 1: tokens, 2: pairs), each column scaled to unit maximum so
+// that the normal equations stay well conditioned.
 inline bool fit_columns(const std::vector<double> (&x)[3], const double* y, int n,
                         const int* cols, int k, double out[3]) {
   double scale[3] = {1.0, 1.0, 1.0};
@@ -88,9 +90,9 @@ inline bool fit_columns(const std::vector<double> (&x)[3], const double* y, int 
   double a[3][3] = {{0}}, b[3] = {0, 0, 0};
   for (int i = 0; i < n; ++i)
     for (int r = 0; r < k; ++r) {
-      const double xr = x[cols[r]][i] / scale[r];
-      b[r] += xr * y[i];
-      for (int c = 0; c < k; ++c) a[r][c] += xr * (x[cols[c]][i] / scale[c]);
+      const double xr = x[cols[r]][i] / scale[r] / y[i];
+      b[r] += xr;  // the weighted target is y / y = 1
+      for (int c = 0; c < k; ++c) a[r][c] += xr * (x[cols[c]][i] / scale[c] / y[i]);
     }
   if (!solve(a, b, k)) return false;
   out[0] = out[1] = out[2] = 0.0;

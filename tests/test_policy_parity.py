@@ -98,7 +98,8 @@ def test_fit_recovers_a_model_and_agrees_with_numpy_least_squares():
     noisy = sec * (1 + 0.02 * rng.standard_normal(40))
     m, err = L.fit_time_model(kv, ch, noisy)
     a = np.stack([np.ones(40), ch, pairs], 1)
-    ref = np.linalg.lstsq(a / a.max(0), noisy, rcond=None)[0] / a.max(0)
+    aw = a / noisy[:, None]                              # relative error: rows weighted by 1/y
+    ref = np.linalg.lstsq(aw / aw.max(0), np.ones(40), rcond=None)[0] / aw.max(0)
     assert np.allclose([m.t_fixed, m.t_token, m.t_pair], ref, rtol=1e-6, atol=0)
     assert 0 < err < 0.15
     # attention-only timings (what this library can measure): the per-token term is dropped
