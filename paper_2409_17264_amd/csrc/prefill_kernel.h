@@ -7,12 +7,14 @@
 //     online softmax   (a lane owns one row: statistics are lane-local)
 //     O^T += V^T P^T   (MFMA, V^T through the transposing LDS read, P^T straight
 //                       from the S^T accumulators)
-// With two wavefronts per SIMD the matrix-core phase of one overlaps the softmax
-// phase of the other.
+// The tile walk is software-pipelined inside every wavefront: the S^T MFMAs of tile
+// j+1 and the O^T MFMAs of tile j form one instruction stream with the softmax
+// arithmetic of tile j spread between them (RowBlock::fused), because the matrix
+// pipe and the vector ALU share an issue port and neither should wait for the other.
 //
 // K/V tiles go HBM -> LDS directly (no registers) with asynchronous 16-byte
-// global loads into a ring of NS stages, gathered page by page through the page
-// table.  Each page row is 16*D*2 contiguous bytes, so every 1 KiB load
+// global loads into a ring of NS stages (K tiles in its low half, V tiles in its
+// high half), gathered page by page through the page table.  Each page row is 16*D*2 contiguous bytes, so every 1 KiB load
 // instruction reads whole rows.  Rows are stored unpadded; bank conflicts are
 // avoided by XOR-swizzling the 16-byte column index with the row index (one
 // pattern for the 16-byte K reads, another for the 8-byte transposing V reads).
