@@ -90,6 +90,19 @@ hipError_t launch_plan(const LaunchPlan& lp, bool split_keys, int d, AttnArgs& a
   m.total_rows = lp.total_rows;
   if (a.n_seq <= kMaxInlineSeq)
     std::memcpy(m.inline_descs, lp.descs.data(), lp.descs.size() * sizeof(SeqDesc));
+  int max_split = 1;
+  for (const SeqDesc& sd : lp.descs) max_split = std::max(max_split, sd.n_split);
+  if (max_split > kWideMergeSplits) {
+    // many KV ranges per row: one workgroup per (row, head), ranges spread over its lanes
+    const int64_t blocks = (int64_t)lp.total_rows * a.h_q;
+    if (d == 128)
+      hipLaunchKernelGGL(split_merge_wide_kernel<128>, dim3((unsigned)blocks), dim3(kThreads), 0,
+                         stream, m);
+    else
+      hipLaunchKernelGGL(split_merge_wide_kernel<64>, dim3((unsigned)blocks), dim3(kThreads), 0,
+                         stream, m);
+    return hipGetLastError();
+  }
   const int64_t threads = (int64_t)lp.total_rows * a.h_q * (d / 4);
   const int grid = (int)ceil_div(threads, kThreads);
   if (d == 128)

@@ -406,3 +406,19 @@ def test_chunk_partial_rejects_bad_arguments():
         with pytest.raises(medha.MedhaError):
             medha.chunk_partial_attn(b.q, b.k_pool, b.v_pool, pt, b.page_table_offs, a["q_row"],
                                      a["chunk_len"], a["kv_len"], a["visible0"], b.scale)
+
+
+# ------------------------------------------ small chunks against a long cache
+@pytest.mark.parametrize("h_q,h_kv,d,prefix,chunk", [(8, 1, 128, 150_000, 32), (8, 2, 64, 70_000, 8),
+                                                     (16, 4, 128, 60_000, 40)])
+def test_small_chunk_long_prefix_many_way_split(h_q, h_kv, d, prefix, chunk):
+    """The regime adaptive chunking ends in (section 3.2): a few dozen tokens against a very long
+    cache.  The KV axis is split tens to hundreds of ways and the partials are merged by the
+    workgroup-per-row merge kernel."""
+    b = wl.make_prefill_batch("small", h_q, h_kv, d, [prefix], [chunk], seed=chunk + d)
+    e, _, _, _ = medha.describe_plan(b.prefix_len, b.chunk_len, h_q, h_kv, d)
+    assert e[0].n_split > 16
+    ro, rl = oracle_prefill(b)
+    b = to_dev(b)
+    out, lse = gpu_prefill(b)
+    check(out, lse, ro, rl, f"small chunk hq{h_q} d{d} P{prefix} c{chunk} split{e[0].n_split}")
