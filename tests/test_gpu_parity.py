@@ -422,3 +422,31 @@ def test_small_chunk_long_prefix_many_way_split(h_q, h_kv, d, prefix, chunk):
     b = to_dev(b)
     out, lse = gpu_prefill(b)
     check(out, lse, ro, rl, f"small chunk hq{h_q} d{d} P{prefix} c{chunk} split{e[0].n_split}")
+
+
+# ------------------------------------------------------------ softmax scale values
+@pytest.mark.parametrize("scale", [0.0, -0.1, 0.5, 1e-3, -2.0])
+def test_softmax_scale_values(scale):
+    """The scale is an argument, not 1/sqrt(d) by construction: zero (uniform weights), negative
+    (its sign is folded into Q inside the kernels), large (sharply peaked rows), tiny.  One
+    batch through both kernels: a chunk of 150 tokens and three decodes."""
+    b = wl.make_prefill_batch("sc", 8, 2, 128, [600, 0, 77, 1000], [150, 1, 1, 1], seed=17,
+                              poison_unused=True)
+    b.scale = scale
+    ro, rl = oracle_prefill(b)
+    b = to_dev(b)
+    out, lse = gpu_prefill(b)
+    # LSE grows with |scale| * |q.k|: keep the absolute tolerance where fp32 can hold it
+    assert np.max(np.abs(rl)) < 2000
+    if abs(scale) < 0.2:
+        check(out, lse, ro, rl, f"scale {scale}")
+        return
+    # Sharply peaked rows: one or two keys carry the row, P is rounded to bf16 (relative 2^-9)
+    # against a reference point that need not be the row maximum, so the dominant weight is
+    # not exactly 1 and |dO| can reach 2^-9 * max|V| * (a few terms) -- the bound below -- while
+    # LSE, summed in fp32 before the rounding, keeps its 1e-3.
+    vmax = float(b.v_pool.float().nan_to_num(0.0).abs().max())
+    eo = float(np.max(np.abs(out - ro)))
+    el = float(np.max(np.abs(lse - rl)))
+    print(f"[parity] scale {scale}: max|dO|={eo:.3e} (bound {2 ** -8 * vmax:.3e}) max|dLSE|={el:.3e}")
+    assert np.isfinite(out).all() and eo <= 2 ** -8 * vmax and el <= LSE_TOL
