@@ -269,12 +269,16 @@ struct RowBlock {
   // maximum: it is moved up (and the accumulators rescaled) only when some row's
   // maximum exceeds it by more than kRescaleSlack, so that p <= 2^kRescaleSlack.  The
   // common factor cancels in O = acc / l and LSE = m + log2(l); after the first few
-  // tiles of a long sequence the rescale practically never runs.  Returns the value
-  // to exponentiate against (0 while the row has seen no key).
-  template <bool MASK>
+  // tiles of a long sequence the rescale practically never runs.  With LAZY false the
+  // reference point follows the maximum exactly (slack 0): the largest probability of
+  // a row is then exactly 1 and loses nothing in the bf16 rounding of P, which is
+  // what rows carried by one or two keys want; the key-split kernel, whose vector
+  // ALUs idle behind the memory stream, runs that way.  Returns the value to
+  // exponentiate against (0 while the row has seen no key).
+  template <bool MASK, bool LAZY = true>
   __device__ __forceinline__ float update_reference(float mx_raw) {
     const float mx = max_halves(mx_raw) * scale_log2;  // scale_log2 >= 0
-    if (__any(mx > m + kRescaleSlack)) {
+    if (__any(mx > m + (LAZY ? kRescaleSlack : 0.f))) {
       const float m_new = fmaxf(m, mx);
       // a row that has seen no key yet keeps m = -inf: nothing to rescale
       const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m - m_new);
@@ -313,7 +317,7 @@ struct RowBlock {
         }
         mx = fmaxf(mx, s[kb][e]);
       }
-    const float m_use = update_reference<MASK>(mx);
+    const float m_use = update_reference<MASK, false>(mx);
 
     float ls = 0.f;
     // P^T operand of slice g: elements 8*(g%2) .. +7 of S^T block g/2.  The row sum is
@@ -467,7 +471,7 @@ struct RowBlock {
           mx = fmaxf(mx, sc[f >> 4][f & 15]);
         }
       }
-      if constexpr (!kSpec && i == kMaxSlots) m_use = update_reference<MASK>(mx);
+      if constexpr (!kSpec && i == kMaxSlots) m_use = update_reference<MASK, false>(mx);
       if constexpr (i >= kMaxSlots && i < kMaxSlots + 4 * kSpan) {
         constexpr int g = (i - kMaxSlots) / kSpan, r = (i - kMaxSlots) % kSpan;
 #pragma unroll
