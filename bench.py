@@ -147,8 +147,8 @@ def cpu_baseline(batch, budget_s=15.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--sections", default="ceilings,main,append,decode,sweep,policy,mixed,cpu")
     args = ap.parse_args()
     if args.gpus != 1:
