@@ -450,3 +450,26 @@ def test_softmax_scale_values(scale):
     el = float(np.max(np.abs(lse - rl)))
     print(f"[parity] scale {scale}: max|dO|={eo:.3e} (bound {2 ** -8 * vmax:.3e}) max|dLSE|={el:.3e}")
     assert np.isfinite(out).all() and eo <= 2 ** -8 * vmax and el <= LSE_TOL
+
+
+# ------------------------------------------------------ seeded random batch mixes
+@pytest.mark.parametrize("seed", range(12))
+def test_random_batches(seed):
+    """Seeded random batches: head counts, head dim, 1..70 sequences (more than 64 puts the
+    descriptors in the workspace), prefixes 0..3000 and chunks 1..260 in any mix, so that
+    sequences of both kernels, split and unsplit, share one call."""
+    rng = np.random.default_rng(1000 + seed)
+    h_kv = int(rng.choice([1, 2, 4, 8]))
+    h_q = h_kv * int(rng.choice([1, 2, 4, 8]))
+    d = int(rng.choice([64, 128]))
+    n = int(rng.choice([1, 2, 5, 17, 70]))
+    prefix = rng.integers(0, 3000, n).astype(np.int32)
+    chunk = np.where(rng.random(n) < 0.5, 1, rng.integers(1, 260, n)).astype(np.int32)
+    if n >= 17:                       # keep the oracle's share of the run short
+        prefix = (prefix // 4).astype(np.int32)
+        chunk = np.minimum(chunk, 40).astype(np.int32)
+    b = to_dev(wl.make_prefill_batch("rnd", h_q, h_kv, d, prefix, chunk, seed=seed + 500,
+                                     poison_unused=True))
+    out, lse = gpu_prefill(b)
+    ro, rl = oracle_prefill(b)
+    check(out, lse, ro, rl, f"random batch seed {seed}: hq{h_q} hkv{h_kv} d{d} n{n}")
