@@ -576,7 +576,7 @@ __device__ __forceinline__ void run_tiles(RowBlock<D>& rb, const AttnArgs& args,
     ld.issue(args, page, tile, kv_total, kv_head, ring.lds_addr + s * kTile,
              ring.lds_addr + (NS + s) * kTile);
   }
-  // page id of the next tile to issue, fetched one step ahead of its use
+  // page id of the next tile to issue
   int page_next = tile_page<D, NW>(pt, min(kt_a + 3, last), kv_total, wave);
   f32x16 s0[2], s1[2];  // scores of the even / odd tiles (counted from kt_a)
   ring_barrier<2 * G::kLoadsPerWaveTile>();  // tile kt_a has landed, for everyone
@@ -595,15 +595,23 @@ __device__ __forceinline__ void run_tiles(RowBlock<D>& rb, const AttnArgs& args,
         // this wavefront's loads of tile cur+1 have landed (tile cur+2 may fly); after the
         // barrier everyone's have, and everyone is done with the stage refilled next
         ring_barrier<G::kLoadsPerWaveTile>();
+        asm volatile("" : "+s"(page_next));  // the page id is first needed here, not before
         const uint32_t nxt = ring.lds_addr + ((s + 3) % NS) * kTile;
         ld.issue(args, page_next, min(cur + 3, last), kv_total, kv_head, nxt, nxt + NS * kTile);
-        page_next = tile_page<D, NW>(pt, min(cur + 4, last), kv_total, wave);
         const char* k_next = ring.base + ((s + 1) % NS) * kTile;
         const char* v_cur = ring.base + s * kTile;  // + the bias in rb.v_off
         if (s & 1)
           rb.template fused<MASK>(k_next, v_cur, s1, s0, cur * G::kTileKeys, half);
         else
           rb.template fused<MASK>(k_next, v_cur, s0, s1, cur * G::kTileKeys, half);
+        // The scalar load of the next page id goes HERE, after the tile's last LDS read has
+        // been consumed and before the barrier: scalar loads and LDS reads share one
+        // counter and scalar loads return out of order, so with one in flight every wait for
+        // an LDS operand becomes a wait for everything -- a stall of a scalar-load latency in
+        // front of the tile's first MFMA.  Here its latency hides behind the barrier.
+        __builtin_amdgcn_sched_barrier(0);
+        page_next = tile_page<D, NW>(pt, min(cur + 4, last), kv_total, wave);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
