@@ -77,3 +77,39 @@ def test_config5_full_size_sampled_rows():
     rows = np.concatenate([np.array([0, 511, 1023]), np.arange(1024, 1024 + 64)]).astype(np.int64)
     ro, rl = oracle_prefill(b, rows)
     check(out[rows], lse[rows], ro, rl, "cfg5 full size: 3 prefill rows + all 64 decodes")
+
+
+def test_config4_full_size_chunk_kvp_and_small_chunk():
+    """The two other launch shapes bench.py times on the 1M-token cache: a 2048-token chunk
+    against 4 page-aligned KV shards (only the last causal) merged with the LSE merge, and a
+    32-token chunk whose KV axis is split 253 ways; both against oracle rows sampled one by one
+    from plain chunked prefill."""
+    b = wl.config4_llama70b_tp(2048, "cuda:0")
+    prefix, chunk, shards = int(b.prefix_len[0]), 2048, 4
+    n = prefix + chunk
+    per = ((n + shards - 1) // shards + 15) // 16 * 16
+    cuts = [min(n, i * per) for i in range(shards + 1)]
+    slices = [b.page_table[lo // 16:(hi + 15) // 16] for lo, hi in zip(cuts[:-1], cuts[1:])]
+    pto = np.concatenate([[0], np.cumsum([len(s) for s in slices])]).astype(np.int64)
+    po, pl = medha.chunk_partial_attn(
+        b.q, b.k_pool, b.v_pool, torch.from_numpy(np.concatenate(slices)).cuda(), pto,
+        np.zeros(shards, np.int32), np.full(shards, chunk, np.int32),
+        np.diff(cuts).astype(np.int32), np.array([prefix + 1 - lo for lo in cuts[:-1]], np.int32),
+        b.scale)
+    o, l = medha.lse_merge(po.view(shards, chunk, b.h_q, b.d), pl.view(shards, chunk, b.h_q))
+    torch.cuda.synchronize()
+    rows = np.array([0, 1000, chunk - 1], np.int64)
+    ro, rl = oracle_prefill(b, rows)
+    check(o.cpu().numpy()[rows], l.cpu().numpy()[rows], ro, rl,
+          "cfg4 c2048 as 4 KV shards + merge, 3 sampled rows x 8 heads")
+    # the same cache, first 32 tokens of the chunk only
+    small = wl.PrefillBatch("cfg4_c32", b.h_q, b.h_kv, b.d, b.prefix_len, np.array([32], np.int32),
+                            b.page_table, b.page_table_offs, b.num_pages, b.q[:32].contiguous(),
+                            b.k_pool, b.v_pool, b.scale)
+    e, _, _, _ = medha.describe_plan(small.prefix_len, small.chunk_len, small.h_q, small.h_kv,
+                                     small.d)
+    assert e[0].n_split > 200
+    out, lse = gpu_prefill(small)
+    rows = np.array([0, 31], np.int64)
+    ro, rl = oracle_prefill(small, rows)
+    check(out[rows], lse[rows], ro, rl, "cfg4 c32 (253-way split), 2 sampled rows x 8 heads")
