@@ -168,7 +168,7 @@ decode_kernel(const AttnArgs args) {
   float* sm_o = reinterpret_cast<float*>(lds);   // [wave][32][D]
   float* sm_ml = sm_o + kWaves * 32 * D;         // [wave][32][2]
   static_assert(kWaves * 32 * (D + 2) * 4 <= G::kLdsBytes, "combine buffer fits");
-  const float lt = sum_halves(rb.l);
+  const float lt = rb.row_sum();
   if (valid) {
     float* op = sm_o + (wave * 32 + col) * D + 4 * half;
 #pragma unroll

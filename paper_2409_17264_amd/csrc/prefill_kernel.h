@@ -176,8 +176,8 @@ struct RowBlock {
   static constexpr int kDBlocks = D / 32;
   bf16x8 q[kSlices];
   f32x16 o[kDBlocks];
-  float m;        // running maximum of scale_log2 * score
-  float l;        // this lane's share of the running sum
+  float m;        // reference point of the exponentials (log2 domain), see update_reference()
+  float l;        // kSpecShare * (this lane's share of the running sum), see add_to_sum()
   int limit;      // last visible key index of the lane's row
   float scale_log2;
   // per-lane LDS byte offsets of the operand reads inside a stage
@@ -264,21 +264,19 @@ struct RowBlock {
     }
   }
 
-  // Row maximum of the (masked) scores against the running reference point m.
-  // m is the reference point of the exponentials, not necessarily the true running
-  // maximum: it is moved up (and the accumulators rescaled) only when some row's
-  // maximum exceeds it by more than kRescaleSlack, so that p <= 2^kRescaleSlack.  The
-  // common factor cancels in O = acc / l and LSE = m + log2(l); after the first few
-  // tiles of a long sequence the rescale practically never runs.  With LAZY false the
-  // reference point follows the maximum exactly (slack 0): the largest probability of
-  // a row is then exactly 1 and loses nothing in the bf16 rounding of P, which is
-  // what rows carried by one or two keys want; the key-split kernel, whose vector
-  // ALUs idle behind the memory stream, runs that way.  Returns the value to
-  // exponentiate against (0 while the row has seen no key).
-  template <bool MASK, bool LAZY = true>
+  // Moves the reference point m of the exponentials up to the row maximum of the
+  // (masked) scores just seen, if that exceeds it, and rescales the accumulators.
+  // m is the point the exponentials are taken against, not necessarily the running
+  // maximum: unmasked tiles are exponentiated against it as it stands (see fused()),
+  // and any common factor cancels in O = acc / l and LSE = m + log2(l).  Whenever this
+  // routine runs, the largest probability of the row so far becomes exactly 1 and so
+  // loses nothing in the bf16 rounding of P, which is what rows carried by one or two
+  // keys need.  Returns the value to exponentiate against (0 while the row has seen
+  // no key).
+  template <bool MASK>
   __device__ __forceinline__ float update_reference(float mx_raw) {
     const float mx = max_halves(mx_raw) * scale_log2;  // scale_log2 >= 0
-    if (__any(mx > m + (LAZY ? kRescaleSlack : 0.f))) {
+    if (__any(mx > m)) {
       const float m_new = fmaxf(m, mx);
       // a row that has seen no key yet keeps m = -inf: nothing to rescale
       const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m - m_new);
@@ -317,7 +315,7 @@ struct RowBlock {
         }
         mx = fmaxf(mx, s[kb][e]);
       }
-    const float m_use = update_reference<MASK, false>(mx);
+    const float m_use = update_reference<MASK>(mx);
 
     float ls = 0.f;
     // P^T operand of slice g: elements 8*(g%2) .. +7 of S^T block g/2.  The row sum is
@@ -344,7 +342,7 @@ struct RowBlock {
       if (g + 2 < kGroups) read_v_slice(v_lds, g + 2, vop[g & 1]);
       __builtin_amdgcn_sched_barrier(0);
     }
-    l += ls;
+    add_to_sum(ls);
   }
 
   // One whole tile: the first V^T operands are requested ahead of phase 1.
@@ -370,14 +368,28 @@ struct RowBlock {
   //
   // Tiles that every row sees in full (MASK false) are therefore exponentiated
   // SPECULATIVELY against the reference point m as it stands, without looking for the
-  // row maximum first: once m has been set from a row's first tile, a later score
-  // exceeds it by more than a few units only in contrived inputs.  The speculation is
-  // checked on the row sums, twice per tile and before any MFMA consumes the
-  // probabilities in question (all p >= 0, so a sum within kSpecLimit bounds each
-  // term, and an overflow to +inf shows as well); a failed check takes the exact
-  // route for those two slices: maximum, move of the reference point, rescale, new
-  // probabilities.  Diagonal tiles (MASK true) always take the exact route.
-  static constexpr float kSpecLimit = 1073741824.f;  // 2^30
+  // row maximum first.  What the speculation must not do is round a probability that
+  // carries a large share of its row: P goes to the matrix cores as bf16 (relative
+  // rounding error up to 2^-8), the row sum is taken over the unrounded values, so the
+  // error of one key's weight reaches O undamped unless that probability is exactly 1
+  // (the row maximum, taken against itself) or small next to the row sum.  The
+  // speculation is therefore checked on the row sums, twice per tile and before any
+  // MFMA consumes the probabilities in question: the lane's sum over the two slices
+  // just exponentiated (all p >= 0, so it bounds each of them; an overflow to +inf or a
+  // NaN shows as well) must not exceed kSpecShare times the lane's sum so far.  The
+  // lane keeps its sum pre-multiplied by kSpecShare (a power of two: exact), so the
+  // check is one comparison of two registers.  A failed check takes the exact route for
+  // those two slices -- maximum, move of the reference point, rescale, new
+  // probabilities -- and evens out the sums of the two lanes that share a row (a lane
+  // whose keys so far happen to weigh little would otherwise keep failing).  The first
+  // few hundred keys of a walk always take that route (the sum is still small), and so
+  // do keys that bring a sizeable share of their row; everything else -- nearly all of
+  // a long walk -- passes.  Diagonal tiles (MASK true) always take the exact route.
+  static constexpr float kSpecShare = 1.f / 16.f;
+
+  __device__ __forceinline__ void add_to_sum(float ls) { l = __builtin_fmaf(ls, kSpecShare, l); }
+  // The row's sum of probabilities relative to the reference point (both lanes of the row).
+  __device__ __forceinline__ float row_sum() const { return sum_halves(l) * (1.f / kSpecShare); }
 
   // Exact recomputation of slices 2*KB and 2*KB+1 (score block KB) after a failed check.
   template <int KB>
@@ -471,7 +483,7 @@ struct RowBlock {
           mx = fmaxf(mx, sc[f >> 4][f & 15]);
         }
       }
-      if constexpr (!kSpec && i == kMaxSlots) m_use = update_reference<MASK, false>(mx);
+      if constexpr (!kSpec && i == kMaxSlots) m_use = update_reference<MASK>(mx);
       if constexpr (i >= kMaxSlots && i < kMaxSlots + 4 * kSpan) {
         constexpr int g = (i - kMaxSlots) / kSpan, r = (i - kMaxSlots) % kSpan;
 #pragma unroll
@@ -490,17 +502,22 @@ struct RowBlock {
       asm volatile("" : "+v"(ls));  // keeps the additions in their slots
       if constexpr (kSpec && (i == 2 * kSpan - 1 || i == 4 * kSpan - 1)) {
         // ls covers the two slices just finished
-        if (__builtin_expect(__any(!(ls <= kSpecLimit)), 0)) {
+        if (__builtin_expect(__any(!(ls <= l)), 0)) {
           respeculate<(i == 2 * kSpan - 1) ? 0 : 1>(sc, pw, ls);
           m_use = m;
+          add_to_sum(ls);
+          l = 0.5f * sum_halves(l);
+          ls = 0.f;
         }
-        l += ls;
+        // (one common addition after the branch: with an addition on each side of it the
+        // register allocation of the whole loop degrades badly)
+        add_to_sum(ls);
         ls = 0.f;
       }
       __builtin_amdgcn_sched_barrier(0);
     };
     static_for<kSlots>(slot);
-    l += ls;
+    add_to_sum(ls);
   }
 };
 
@@ -697,7 +714,7 @@ __global__ void __launch_bounds__(512) prefill_kernel(const AttnArgs args) {
   float* l_base = direct ? args.lse : args.part_lse;
   const int64_t row_base =
       direct ? (int64_t)sd.out_row : (int64_t)sd.part_row + (int64_t)split * sd.chunk_len;
-  const float lt = sum_halves(rb.l);
+  const float lt = rb.row_sum();
   const float inv = lt > 0.f ? 1.f / lt : 0.f;
   const float lse = lt > 0.f ? (rb.m + fast_log2(lt)) * kLn2 : -INFINITY;
   if (valid) {

@@ -35,6 +35,29 @@ def oracle_prefill(batch, rows=None):
                                        batch.scale, rows)
 
 
+def edge_rows(batch, seed, head=8, tail=8, rand=16, edges=8, seq=0):
+    """Token rows of sequence `seq` to compare one by one at full size: the first `head` and
+    last `tail` rows and `rand` seeded random ones (wl.sample_rows), plus up to `edges` rows
+    that sit where the kernels change regime: on either side of a 256-row workgroup edge and
+    of a 128-row one (row = token * group + head-in-group), and rows whose last visible key is
+    the last or the first key of a 64-key tile."""
+    c, p = int(batch.chunk_len[seq]), int(batch.prefix_len[seq])
+    g = batch.h_q // batch.h_kv
+    rows = set(wl.sample_rows(c, seed, head, tail, rand).tolist())
+    rng = np.random.Generator(np.random.PCG64(seed + 77))
+    cand = []
+    for rows_per_wg in (256, 128):
+        tok = max(1, rows_per_wg // g)
+        cand += [t + o for t in range(tok, c, tok) for o in (-1, 0)]
+    first = (-(p + 1)) % 64                 # first row whose last visible key ends a tile
+    cand += [j + o for j in range(first, c, 64) for o in (0, 1) if j + o < c]
+    cand = sorted(set(cand) - rows)
+    if cand:
+        pick = rng.choice(len(cand), size=min(edges, len(cand)), replace=False)
+        rows |= {cand[i] for i in pick}
+    return np.array(sorted(rows), np.int64)
+
+
 def check(out, lse, ref_out, ref_lse, what=""):
     assert np.isfinite(out).all(), f"{what}: non-finite O"
     fin = np.isfinite(ref_lse)

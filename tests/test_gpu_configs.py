@@ -7,7 +7,7 @@ import torch
 import oracle
 import paper_2409_17264_amd as medha
 from paper_2409_17264_amd import workloads as wl
-from tests.gpu_util import check, gpu_prefill, oracle_prefill, to_dev
+from tests.gpu_util import check, edge_rows, gpu_prefill, oracle_prefill, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -39,20 +39,23 @@ def test_config5_scaled_mixed_batch_full_oracle():
 def test_config2_full_size_sampled_rows():
     b = wl.config2_llama8b("cuda:0")
     out, lse = gpu_prefill(b)
-    rows = wl.sample_rows(b.tokens, 2, 4, 4, 8)
+    rows = edge_rows(b, 2, 16, 16, 32, 16)
     ro, rl = oracle_prefill(b, rows)
-    check(out[rows], lse[rows], ro, rl, "cfg2 full size, 16 sampled rows x 32 heads")
+    check(out[rows], lse[rows], ro, rl, f"cfg2 full size, {len(rows)} sampled rows x 32 heads")
 
 
-def test_config4_full_size_sampled_rows():
-    for chunk in (512, 2048):
-        b = wl.config4_llama70b_tp(chunk, "cuda:0")
-        out, lse = gpu_prefill(b)
-        rows = np.array([0, chunk // 2 + 1, chunk - 1], np.int64)
-        ro, rl = oracle_prefill(b, rows)
-        check(out[rows], lse[rows], ro, rl, f"cfg4 c{chunk} full size, 3 sampled rows x 8 heads")
-        del b
-        torch.cuda.empty_cache()
+@pytest.mark.parametrize("chunk", [512, 1024, 2048, 4096, 8192])
+def test_config4_full_size_sampled_rows(chunk):
+    """Every chunk length of the adaptive-chunk sweep at the 1,048,576-token prefix, in the
+    launch shape the benchmark times (16-way down to no KV split; 256-row workgroups)."""
+    b = wl.config4_llama70b_tp(chunk, "cuda:0")
+    out, lse = gpu_prefill(b)
+    rows = edge_rows(b, 40 + chunk, 8, 8, 16, 8)
+    ro, rl = oracle_prefill(b, rows)
+    check(out[rows], lse[rows], ro, rl,
+          f"cfg4 c{chunk} full size, {len(rows)} sampled rows x 8 heads")
+    del b
+    torch.cuda.empty_cache()
 
 
 def test_config3_full_size_kvp_decode():
@@ -74,9 +77,11 @@ def test_config3_full_size_kvp_decode():
 def test_config5_full_size_sampled_rows():
     b = wl.config5_mixed("cuda:0")
     out, lse = gpu_prefill(b)
-    rows = np.concatenate([np.array([0, 511, 1023]), np.arange(1024, 1024 + 64)]).astype(np.int64)
+    pre = edge_rows(b, 5, 16, 16, 32, 8)
+    rows = np.concatenate([pre, np.arange(1024, 1024 + 64)]).astype(np.int64)
     ro, rl = oracle_prefill(b, rows)
-    check(out[rows], lse[rows], ro, rl, "cfg5 full size: 3 prefill rows + all 64 decodes")
+    check(out[rows], lse[rows], ro, rl,
+          f"cfg5 full size: {len(pre)} prefill rows + all 64 decodes")
 
 
 def test_config4_full_size_chunk_kvp_and_small_chunk():
