@@ -23,8 +23,10 @@ The same JSON line also carries, each measured in its own timed loop:
   mixed    one 1024-token prefill chunk at a 524,288-token prefix plus 64
            decodes in one call.
   ceilings what the same device sustains, in the same run, on an MFMA-only loop
-           (N(0,1) bf16 operands) and on a 4 GiB streaming read: context for
-           the data-sheet peaks the roofline fractions use;
+           (N(0,1) bf16 operands) and on a 4 GiB HBM -> LDS stream with 128 KiB
+           in flight per compute unit and no arithmetic: context for the
+           data-sheet peaks the roofline fractions use;
+every entry with its own `roofline` block (bound, achieved, peak, frac, kernel);
 and `cpu_baseline`: the fp64 CPU oracle timed on a bounded sample of rows of
 the headline workload on this machine's host cores (a reported baseline only).
 
@@ -51,21 +53,57 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def settle(fn, window=6, tol=0.02, max_steps=400, max_seconds=3.0):
+    """Untimed launches until the device's clocks have settled: after an idle period of a few
+    milliseconds kernel durations on this part swing by up to +30 % for the next 10-20 launches
+    (measured), and the first launch after any synchronisation runs about 4 % long.  Runs `fn`
+    in groups of `window` launches, each launch between its own pair of HIP events, until the
+    durations of a group (its first launch left out) agree within `tol` with one another and
+    with the group before, or a bound is hit.  Returns the number of launches made; they are
+    outside every timed region."""
+    import torch
+    done, prev = 0, None
+    t0 = time.perf_counter()
+    while done < max_steps and time.perf_counter() - t0 < max_seconds:
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(window)]
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        done += window
+        per = np.array([a.elapsed_time(b) for a, b in ev])[1:]
+        mean = float(per.mean())
+        if (per.max() - per.min()) <= tol * per.min() and prev is not None \
+                and abs(mean - prev) <= tol * prev:
+            break
+        prev = mean
+    return done
+
+
 def time_calls(fn, steps, warmup):
-    """Milliseconds per call.  The timed region is `steps` calls back to back between two HIP
-    events on torch's current stream (the stream the library launches on) and between two
-    device synchronisations (wall clock); nothing else is enqueued inside it -- an event pair
-    per step costs about 10 us of idle GPU per step.  Minimum and median come from a second,
+    """Milliseconds per call.  First settle() (untimed, count disclosed), then `warmup` untimed
+    calls, then the timed region: `steps` calls back to back between two HIP events on torch's
+    current stream (the stream the library launches on) and between two device
+    synchronisations (wall clock); nothing else is enqueued inside it -- an event pair per step
+    costs about 10 us of idle GPU per step.  Everything the host has to do (event objects, the
+    interpreter's garbage collection) is done before the warm-up calls, so that the device is
+    not left idle between them and the timed region.  Minimum and median come from a second,
     shorter loop with one event pair per step."""
     import gc
     import torch
-    for _ in range(warmup):
-        fn()
     first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    # as timeit does: no cyclic-GC pause of the interpreter inside the timed region
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(min(steps, 20))]
+    # as timeit does: no cyclic-GC pause of the interpreter inside the timed region (nor
+    # between the settling launches and it: a pause of a few milliseconds unsettles the clocks)
     gc.collect()
     gc.disable()
     try:
+        settled = settle(fn)
+        for _ in range(warmup):
+            fn()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         first.record()
@@ -74,8 +112,6 @@ def time_calls(fn, steps, warmup):
         last.record()
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(min(steps, 20))]
         for a, b in ev:
             a.record()
             fn()
@@ -87,7 +123,22 @@ def time_calls(fn, steps, warmup):
     if os.environ.get("BENCH_DEBUG"):
         log("per-step ms:", np.round(per, 3).tolist())
     return {"wall_ms_per_step": wall_ms / steps, "event_ms_mean": first.elapsed_time(last) / steps,
-            "event_ms_min": float(per.min()), "event_ms_median": float(np.median(per))}
+            "event_ms_min": float(per.min()), "event_ms_median": float(np.median(per)),
+            "settle_steps": settled}
+
+
+def roofline(bound, achieved, kernel, t, traffic_profile=None):
+    """The roofline block of one measurement: `achieved` = algorithmic flops (or bytes) per
+    call / mean duration of the call between HIP events over the timed region, against the
+    published peak of the MI355X; `traffic` = HBM bytes per launch from the rocprofv3 counter
+    summary kept under profiles/ (None where no such summary is kept)."""
+    peak, unit = (PEAK_BF16_TFLOPS, "TFLOP/s") if bound == "mfma" else (PEAK_HBM_GBPS, "GB/s")
+    return {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+            "frac": achieved / peak,
+            "traffic": traffic_from_profile(traffic_profile) if traffic_profile else None,
+            "kernel": kernel, "event_ms_mean": t["event_ms_mean"],
+            "event_ms_median": t["event_ms_median"], "event_ms_min": t["event_ms_min"],
+            "settle_steps": t["settle_steps"]}
 
 
 def prefill_runner(batch):
@@ -180,7 +231,9 @@ def main():
     ceilings = None
     if "ceilings" in sections:
         # what this device sustains on nothing but bf16 MFMAs (N(0,1) operands: switching
-        # power, and with it the clock, depends on the data) and on nothing but reads
+        # power, and with it the clock, depends on the data) and on nothing but streaming HBM
+        # into LDS the way the key-split kernel does (128 KiB in flight per compute unit)
+        from paper_2409_17264_amd import yardstick
         g = torch.Generator(device="cpu").manual_seed(99)
         ops = torch.randn(5 * 64 * 8, generator=g).to(torch.bfloat16).cuda()
         blocks = props.multi_processor_count
@@ -189,19 +242,20 @@ def main():
         fl = [0.0]
 
         def run_mfma():
-            fl[0] = medha.ceiling_mfma_bf16(ops, blocks, iters, sink)
+            fl[0] = yardstick.mfma_bf16(ops, blocks, iters, sink)
         t = time_calls(run_mfma, 10, 3)
         mfma_tf = fl[0] / (t["event_ms_mean"] * 1e-3) / 1e12
         src = torch.empty(1 << 32, dtype=torch.uint8, device="cuda").fill_(3)
-        rblocks = blocks * 8
-        rsink = torch.empty(rblocks * 256 * 16, dtype=torch.uint8, device="cuda")
-        t2 = time_calls(lambda: medha.ceiling_stream_read(src, rblocks, rsink), 10, 3)
+        rsink = torch.empty(blocks * 256, dtype=torch.int32, device="cuda")
+        t2 = time_calls(lambda: yardstick.stream_lds(src, blocks, rsink), 10, 3)
         read_gbps = src.numel() / (t2["event_ms_mean"] * 1e-3) / 1e9
         log(f"ceilings: MFMA-only bf16 (N(0,1) operands) {mfma_tf:.0f} TFLOP/s "
-            f"({t['event_ms_mean']:.3f} ms); streaming read {read_gbps:.0f} GB/s")
-        ceilings = {"mfma_bf16_tflops": mfma_tf, "stream_read_gbps": read_gbps,
+            f"({t['event_ms_mean']:.3f} ms); HBM->LDS stream {read_gbps:.0f} GB/s")
+        ceilings = {"mfma_bf16_tflops": mfma_tf, "stream_lds_gbps": read_gbps,
                     "note": "same device, same run: an MFMA-only loop with N(0,1) bf16 operands "
-                            "and a 4 GiB streaming read; context for the data-sheet peaks"}
+                            "and a 4 GiB HBM->LDS stream (one workgroup of 4 wavefronts per "
+                            "compute unit, 128 KiB in flight each, no arithmetic); context for "
+                            "the data-sheet peaks"}
         del src, rsink, sink, ops
         torch.cuda.empty_cache()
     # ------------------------------------------------------------- headline
@@ -212,7 +266,8 @@ def main():
     ms = t["wall_ms_per_step"]
     tflops = flops / (ms * 1e-3) / 1e12
     kern_tflops = flops / (t["event_ms_mean"] * 1e-3) / 1e12
-    log(f"main: {ms:.4f} ms/step wall, {t['event_ms_mean']:.4f} ms events -> {tflops:.1f} TFLOP/s")
+    log(f"main: {ms:.4f} ms/step wall, {t['event_ms_mean']:.4f} ms events (median "
+        f"{t['event_ms_median']:.4f}, {t['settle_steps']} settling launches) -> {tflops:.1f} TFLOP/s")
     result.update({
         "metric": "chunked-prefill attn TFLOP/s + decode KV-read GB/s, % of MI355X roofline",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -221,11 +276,9 @@ def main():
         "config": {"workload": "cfg2 Llama-3-8B layer chunked prefill: 32 q / 8 kv heads, d 128, "
                                "prefix 32768 + chunk 2048, page 16, shuffled 2176-page table",
                    "algorithmic_flops": flops, "kv_bytes": b.algorithmic_kv_bytes()},
-        "roofline": {"bound": "mfma", "achieved": kern_tflops, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": kern_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": traffic_from_profile("prefill_kernel_cfg2_pmc.txt"),
-                     "kernel": "prefill_kernel<128,8,4>", "event_ms_mean": t["event_ms_mean"],
-                     "event_ms_min": t["event_ms_min"]},
+        "roofline": roofline("mfma", kern_tflops, "prefill_kernel<128,8,4>", t,
+                             "prefill_kernel_cfg2_pmc.txt"),
+        "settle_steps": t["settle_steps"], "ms_per_step_median": t["event_ms_median"],
     })
     if ceilings is not None:
         result["ceilings"] = ceilings
@@ -280,15 +333,15 @@ def main():
         result["decode"] = {
             "workload": "cfg3 KVP decode: 1 query, 32 q / 8 kv heads, d 128, 1,048,576-token "
                         "context as 4 shards of 262,144 + LSE merge",
-            "ms": t["event_ms_mean"], "ms_min": t["event_ms_min"], "value": gbps, "unit": "GB/s",
+            "ms": t["event_ms_mean"], "ms_min": t["event_ms_min"],
+            "ms_median": t["event_ms_median"], "value": gbps, "unit": "GB/s",
             "kv_bytes": c.algorithmic_kv_bytes(),
-            "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                         "frac": gbps / PEAK_HBM_GBPS,
-                         "traffic": traffic_from_profile("decode_kernel_cfg3_pmc.txt"),
-                         "kernel": "decode_kernel<128> (+ split_merge_kernel, lse_merge_kernel)"}}
+            "roofline": roofline("hbm", gbps,
+                                 "decode_kernel<128> (+ split_merge_kernel, lse_merge_kernel)", t,
+                                 "decode_kernel_cfg3_pmc.txt")}
         if ceilings is not None:
             result["decode"]["roofline"]["frac_of_measured_ceiling"] = \
-                gbps / ceilings["stream_read_gbps"]
+                gbps / ceilings["stream_lds_gbps"]
         del c, pt, po, pl, ws
         torch.cuda.empty_cache()
 
@@ -305,9 +358,15 @@ def main():
             t = time_calls(run, max(3, args.steps // 3), 2)
             tf = bb.algorithmic_flops() / (t["event_ms_mean"] * 1e-3) / 1e12
             log(f"sweep c={chunk}: {t['event_ms_mean']:.3f} ms -> {tf:.1f} TFLOP/s")
+            e, _, _, _ = medha.describe_plan(bb.prefix_len, bb.chunk_len, bb.h_q, bb.h_kv, bb.d)
+            kern = f"prefill_kernel<128,{8 if e[0].rows_per_wg == 256 else 4},4>" + (
+                "" if e[0].n_split == 1 else f" x {e[0].n_split} KV ranges + split merge")
             sweep.append({"chunk": chunk, "ms": t["event_ms_mean"], "tflops": tf,
                           "frac_of_peak": tf / PEAK_BF16_TFLOPS,
-                          "us_per_token": t["event_ms_mean"] * 1e3 / chunk})
+                          "us_per_token": t["event_ms_mean"] * 1e3 / chunk,
+                          "algorithmic_flops": bb.algorithmic_flops(),
+                          "roofline": roofline("mfma", tf, kern, t,
+                                               f"prefill_kernel_cfg4_c{chunk}_pmc.txt")})
         per_tok = {p["chunk"]: p["us_per_token"] for p in sweep}
         result["sweep"] = {"workload": "cfg4 Llama-3-70B TP8 share: 8 q / 1 kv head, d 128, "
                                        "prefix 1,048,576", "points": sweep,
@@ -344,8 +403,16 @@ def main():
             tm = time_calls(lambda: medha.lse_merge(allo, alll, mo, ml), 10, 3)
             log(f"kvp chunk {chunk} / {shards} shards: shard {t['event_ms_mean']:.3f} ms, "
                 f"merge {tm['event_ms_mean'] * 1e3:.1f} us")
+            shard_flops = 4.0 * base.d * base.h_q * (
+                chunk * float(int(base.prefix_len[0]) - lo) + chunk * (chunk + 1) / 2.0)
+            shard_tf = shard_flops / (t["event_ms_mean"] * 1e-3) / 1e12
+            merge_bytes = 4.0 * chunk * base.h_q * (base.d + 1) * (shards + 1)
             kvp.append({"shards": shards, "shard_keys": n - lo, "shard_ms": t["event_ms_mean"],
-                        "merge_us": tm["event_ms_mean"] * 1e3})
+                        "merge_us": tm["event_ms_mean"] * 1e3, "shard_flops": shard_flops,
+                        "roofline": roofline("mfma", shard_tf, "prefill_kernel<128,8,4>", t),
+                        "merge_roofline": roofline(
+                            "hbm", merge_bytes / (tm["event_ms_mean"] * 1e-3) / 1e9,
+                            "lse_merge_kernel", tm)})
             del po, pl, ws, allo, alll, mo, ml
         if "policy" in sections:
             # the scheduling helpers on THIS device's timings: fit the runtime model to the sweep
@@ -435,7 +502,17 @@ def main():
             "prefill_part_alone_ms": tp["event_ms_mean"],
             "prefill_part_alone_tflops": pf / (tp["event_ms_mean"] * 1e-3) / 1e12,
             "decode_part_alone_ms": td["event_ms_mean"],
-            "decode_part_alone_gbps": dec_bytes / (td["event_ms_mean"] * 1e-3) / 1e9}
+            "decode_part_alone_gbps": dec_bytes / (td["event_ms_mean"] * 1e-3) / 1e9,
+            "roofline": roofline("mfma", (pf + 4.0 * m.d * m.h_q * float(
+                m.meta["decode_lens"].sum())) / (t["event_ms_mean"] * 1e-3) / 1e12,
+                "whole call: prefill_kernel<128,8,4> + decode_kernel<128> + split merges", t,
+                "mixed_cfg5_pmc.txt"),
+            "prefill_part_roofline": roofline(
+                "mfma", pf / (tp["event_ms_mean"] * 1e-3) / 1e12,
+                "prefill_kernel<128,8,4> x 2 KV ranges + split merge", tp),
+            "decode_part_roofline": roofline(
+                "hbm", dec_bytes / (td["event_ms_mean"] * 1e-3) / 1e9,
+                "decode_kernel<128> + split merge", td)}
         del only_prefill, only_decode, run_p, run_d
         del m, run
         torch.cuda.empty_cache()

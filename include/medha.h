@@ -52,7 +52,7 @@ extern "C" {
 
 #define MEDHA_OK 0
 #define MEDHA_ERR_INVALID_ARG (-1)  /* null pointer, bad length, bad head counts, misalignment */
-#define MEDHA_ERR_UNSUPPORTED (-2)  /* page_size != 16, head_dim not 64/128, group too large   */
+#define MEDHA_ERR_UNSUPPORTED (-2)  /* page_size != 16, head_dim not 64/128                     */
 #define MEDHA_ERR_WORKSPACE (-3)    /* workspace missing, misaligned or too small              */
 #define MEDHA_ERR_HIP (-4)          /* a HIP runtime call failed                               */
 
@@ -88,10 +88,13 @@ typedef struct medha_kv_cache {
  *   lse              dev  fp32 [sum chunk_len][num_q_heads]
  *   workspace        dev, 256-byte aligned, at least
  *                    medha_chunked_prefill_workspace_bytes(...) bytes; contents
- *                    are scratch (split-KV partials and the launch plan).
+ *                    are scratch (split-KV partials); may be NULL when that
+ *                    size is <= 256 (nothing is split).
  *
  * Work is split over query tiles and, when those are too few to fill the GPU,
- * also over KV ranges whose partials are merged on the same stream.
+ * also over KV ranges whose partials are merged on the same stream.  Sequence
+ * descriptors travel in the kernel arguments, 64 per launch: a larger batch takes
+ * several launches, and no call ever copies from host memory or blocks the host.
  */
 int medha_chunked_prefill_attn(const void* q, const medha_kv_cache* kv, const int32_t* page_table,
                                const int64_t* page_table_offs, const int32_t* prefix_len,
@@ -112,7 +115,7 @@ size_t medha_chunked_prefill_workspace_bytes(const int32_t* prefix_len, const in
  * attends, without a mask, to tokens [0, kv_len[i]) of the paged sequence given
  * by its page-table slice.  A KV-parallel shard is an item whose slice starts
  * at the shard's first page (shards start on page boundaries).  kv_len 0 is
- * allowed and yields O = 0, LSE = -inf.  num_q_heads / num_kv_heads <= 32.
+ * allowed and yields O = 0, LSE = -inf.
  *
  *   q                dev  bf16 [num_queries][num_q_heads][head_dim], 16-byte aligned
  *   page_table       dev  int32, concatenated slices
@@ -241,32 +244,6 @@ int medha_describe_plan(const int32_t* prefix_len, const int32_t* chunk_len, int
 
 int medha_describe_slot(int32_t slot, int32_t num_kv_heads, int32_t n_split, int32_t n_row_tiles,
                         int32_t* kv_head, int32_t* split, int32_t* row_tile);
-
-/*
- * Yardsticks for the measurement harness (not part of the attention path): what
- * the device at hand sustains when it does nothing but bf16 matrix instructions,
- * and nothing but streaming reads, to set beside the data-sheet peaks the
- * roofline uses.  Both only enqueue one kernel on hip_stream.
- *
- * medha_ceiling_mfma_bf16: `blocks` workgroups of 512 threads; every wavefront
- * chains `iters` rounds of 4 independent 32x32x16 bf16 matrix instructions on
- * operands taken from `operands` (device, 16-byte aligned, at least 5120 bytes
- * of bf16 values of the caller's choice: switching power depends on the data).
- * Work done: blocks * 8 * iters * 4 * 32768 flop.  `sink` (device, at least
- * blocks * 512 floats) receives checksums.
- *
- * medha_ceiling_stream_read: `blocks` workgroups of 256 threads read `bytes`
- * (a multiple of 16) from `src` once, 16 bytes per lane per load; `sink` (device,
- * 16-byte aligned, at least blocks * 4096 bytes) receives checksums.
- *
- * Errors: MEDHA_ERR_INVALID_ARG for null / misaligned / non-positive arguments,
- * MEDHA_ERR_WORKSPACE for a sink that is too small, MEDHA_ERR_HIP for a failed launch.
- */
-int medha_ceiling_mfma_bf16(const void* operands, size_t operand_bytes, int32_t blocks,
-                            int32_t iters, float* sink, size_t sink_floats, void* hip_stream);
-
-int medha_ceiling_stream_read(const void* src, size_t bytes, int32_t blocks, void* sink,
-                              size_t sink_bytes, void* hip_stream);
 
 /* Static, human-readable text for a return code. */
 const char* medha_strerror(int code);

@@ -6,8 +6,6 @@ The library is loaded on first use and a missing library is an error.
 """
 from .binding import (  # noqa: F401
     MedhaError,
-    ceiling_mfma_bf16,
-    ceiling_stream_read,
     chunk_partial_attn,
     chunk_partial_workspace_bytes,
     chunked_prefill_attn,

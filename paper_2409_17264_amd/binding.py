@@ -28,8 +28,6 @@ EXPORTS = (
     "medha_kv_append",
     "medha_describe_plan",
     "medha_describe_slot",
-    "medha_ceiling_mfma_bf16",
-    "medha_ceiling_stream_read",
     "medha_strerror",
     "medha_abi_version",
 )
@@ -95,10 +93,6 @@ def load_library():
     lib.medha_describe_slot.restype = ctypes.c_int
     lib.medha_describe_slot.argtypes = [i32, i32, i32, i32, ctypes.POINTER(i32),
                                         ctypes.POINTER(i32), ctypes.POINTER(i32)]
-    lib.medha_ceiling_mfma_bf16.restype = ctypes.c_int
-    lib.medha_ceiling_mfma_bf16.argtypes = [vp, sz, i32, i32, vp, sz, vp]
-    lib.medha_ceiling_stream_read.restype = ctypes.c_int
-    lib.medha_ceiling_stream_read.argtypes = [vp, sz, i32, vp, sz, vp]
     lib.medha_strerror.restype = ctypes.c_char_p
     lib.medha_strerror.argtypes = [ctypes.c_int]
     lib.medha_abi_version.restype = ctypes.c_int
@@ -328,21 +322,3 @@ def kv_append(k_new: torch.Tensor, v_new: torch.Tensor, k_pool: torch.Tensor,
     assert int(offs[-1]) <= page_table.numel()
     _check(lib.medha_kv_append(_dp(k_new), _dp(v_new), ctypes.byref(kv), _dp(page_table),
                                _hp(offs), _hp(pre), _hp(chk), batch, _stream()))
-
-
-def ceiling_mfma_bf16(operands: torch.Tensor, blocks: int, iters: int, sink: torch.Tensor) -> float:
-    """Enqueue the matrix-instruction yardstick; returns the flop it performs."""
-    assert operands.is_cuda and operands.dtype == torch.bfloat16 and operands.is_contiguous()
-    assert sink.is_cuda and sink.dtype == torch.float32 and sink.is_contiguous()
-    _check(load_library().medha_ceiling_mfma_bf16(
-        _dp(operands), operands.numel() * 2, blocks, iters, _dp(sink), sink.numel(), _stream()))
-    return float(blocks) * 8 * iters * 4 * 32768
-
-
-def ceiling_stream_read(src: torch.Tensor, blocks: int, sink: torch.Tensor) -> float:
-    """Enqueue the streaming-read yardstick; returns the bytes it reads."""
-    assert src.is_cuda and src.is_contiguous() and sink.is_cuda and sink.is_contiguous()
-    nbytes = src.numel() * src.element_size()
-    _check(load_library().medha_ceiling_stream_read(
-        _dp(src), nbytes, blocks, _dp(sink), sink.numel() * sink.element_size(), _stream()))
-    return float(nbytes)

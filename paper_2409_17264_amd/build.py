@@ -1,4 +1,5 @@
-"""Compile the HIP library for gfx950 into paper_2409_17264_amd/libmedha.so.
+"""Compile the HIP libraries for gfx950: csrc/medha.hip into libmedha.so (the product)
+and csrc/yardstick.hip into libmedha_yardstick.so (the benchmark's yardsticks).
 
 Run as ``python -m paper_2409_17264_amd.build``; also called by
 ``__graft_entry__.build()``.  hipcc cross-compiles without a GPU.
@@ -12,6 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libmedha.so")
+# source file -> shared library
+TARGETS = {"medha.hip": LIB, "yardstick.hip": os.path.join(HERE, "libmedha_yardstick.so")}
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -20,22 +23,22 @@ HIPCC_FLAGS = [
 ]
 
 
-def sources():
-    return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
-
-
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", INCLUDE, "-I", CSRC] + sources() + ["-o", LIB]
-    if verbose:
-        print(" ".join(cmd))
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        sys.stderr.write(res.stdout + res.stderr)
-        raise RuntimeError("hipcc failed")
-    if verbose and res.stderr:
-        lines = [l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l]
-        sys.stderr.write("\n".join(lines) + "\n")
+    found = sorted(os.path.basename(p) for p in glob.glob(os.path.join(CSRC, "*.hip")))
+    assert found == sorted(TARGETS), f"every .hip source needs a target: {found}"
+    for src, lib in TARGETS.items():
+        cmd = [hipcc] + HIPCC_FLAGS + ["-I", INCLUDE, "-I", CSRC, os.path.join(CSRC, src),
+                                       "-o", lib]
+        if verbose:
+            print(" ".join(cmd))
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            sys.stderr.write(res.stdout + res.stderr)
+            raise RuntimeError(f"hipcc failed on {src}")
+        if verbose and res.stderr:
+            lines = [l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l]
+            sys.stderr.write("\n".join(lines) + "\n")
     return LIB
 
 

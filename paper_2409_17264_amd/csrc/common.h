@@ -22,7 +22,7 @@ constexpr int kThreads = 256;     // threads per workgroup (4 wavefronts of 64)
 constexpr int kWaves = 4;
 constexpr int kXcds = 8;          // accelerator dies; workgroup i is dispatched to die i % 8
 constexpr int kPrefillStages = 4;  // K/V tiles in flight per workgroup (LDS ring)
-constexpr int kMaxInlineSeq = 64; // sequence descriptors that travel as kernel arguments
+constexpr int kMaxInlineSeq = 64; // sequence descriptors per kernel launch (they travel as kernel arguments)
 constexpr int kWideMergeSplits = 16;  // more KV ranges per row than this: the wide merge kernel
 constexpr float kRescaleSlack = 8.f;  // log2 units a row maximum may exceed the softmax reference
 constexpr float kLog2e = 1.4426950408889634f;
@@ -52,9 +52,9 @@ struct SeqDesc {
 };
 static_assert(sizeof(SeqDesc) == 56, "SeqDesc layout");
 
-// Kernel arguments of the attention kernels.  Up to kMaxInlineSeq descriptors
-// ride in the argument block itself (no host-to-device copy, no
-// synchronisation); larger batches put them in device memory (descs != null).
+// Kernel arguments of the attention kernels.  The sequence descriptors ride in the
+// argument block itself (no host-to-device copy, no synchronisation); a batch of more
+// than kMaxInlineSeq sequences takes several launches.
 struct AttnArgs {
   const __bf16* q;
   const __bf16* k_pool;
@@ -64,7 +64,6 @@ struct AttnArgs {
   float* lse;
   float* part_o;    // split-KV partial outputs  [part rows][h_q][d]
   float* part_lse;  // split-KV partial LSEs     [part rows][h_q]
-  const SeqDesc* descs;
   int32_t n_seq;
   int32_t h_q;
   int32_t h_kv;
@@ -79,7 +78,6 @@ struct MergeArgs {
   const float* part_lse;
   float* out;
   float* lse;
-  const SeqDesc* descs;
   int32_t n_seq;
   int32_t h_q;
   int32_t total_rows;  // token rows of all sequences of the launch

@@ -78,7 +78,7 @@ decode_kernel(const AttnArgs args) {
   using G = DecodeGeom<D>;
   __shared__ __attribute__((aligned(1024))) char lds[G::kLdsBytes];
 
-  const SeqDesc* descs = args.descs ? args.descs : args.inline_descs;
+  const SeqDesc* descs = args.inline_descs;
   const SeqDesc sd = uniform(descs[find_seq_slot(descs, args.n_seq, blockIdx.x)]);
   // one row tile per sequence here, so a slot is just (KV head, split)
   const SlotItem it = decode_slot(blockIdx.x - sd.work_start, args.h_kv, sd.n_split, 1);

@@ -9,7 +9,6 @@
 #include <vector>
 
 #include "append_kernel.h"
-#include "ceiling_kernels.h"
 #include "common.h"
 #include "decode_kernel.h"
 #include "merge_kernel.h"
@@ -52,70 +51,77 @@ hipError_t launch_prefill(const AttnArgs& a, int grid, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// Launches one mode's sequences, at most kMaxInlineSeq per kernel launch: the descriptors of
+// a group travel in the kernel arguments with their workgroup slots and row ranks counted
+// from the group's first sequence, followed by the merge of that group's split-KV partials.
 hipError_t launch_plan(const LaunchPlan& lp, bool split_keys, int d, AttnArgs& a,
-                       void* descs_dev, hipStream_t stream) {
+                       hipStream_t stream) {
   if (lp.descs.empty() || lp.n_slots == 0) return hipSuccess;
-  a.n_seq = (int)lp.descs.size();
-  a.descs = nullptr;
-  if (a.n_seq <= kMaxInlineSeq) {
-    std::memcpy(a.inline_descs, lp.descs.data(), lp.descs.size() * sizeof(SeqDesc));
-  } else {
-    // Pageable source: the runtime has consumed the host buffer when this returns.
-    hipError_t e = hipMemcpyAsync(descs_dev, lp.descs.data(), lp.descs.size() * sizeof(SeqDesc),
-                                  hipMemcpyHostToDevice, stream);
+  const int n_all = (int)lp.descs.size();
+  for (int g0 = 0; g0 < n_all; g0 += kMaxInlineSeq) {
+    const int n = std::min(kMaxInlineSeq, n_all - g0);
+    const int slot0 = lp.descs[g0].work_start, rank0 = lp.descs[g0].row_rank;
+    const int slot1 = g0 + n < n_all ? lp.descs[g0 + n].work_start : lp.n_slots;
+    const int rank1 = g0 + n < n_all ? lp.descs[g0 + n].row_rank : lp.total_rows;
+    a.n_seq = n;
+    int max_split = 1;
+    for (int i = 0; i < n; ++i) {
+      SeqDesc& sd = a.inline_descs[i];
+      sd = lp.descs[g0 + i];
+      sd.work_start -= slot0;
+      sd.row_rank -= rank0;
+      max_split = std::max(max_split, sd.n_split);
+    }
+    const int grid = slot1 - slot0;
+    if (grid <= 0) continue;
+    hipError_t e;
+    if (split_keys) {
+      e = d == 128 ? launch_decode<128>(a, grid, stream) : launch_decode<64>(a, grid, stream);
+    } else if (lp.q_blocks == 2) {
+      e = d == 128 ? launch_prefill<128, 8>(a, grid, stream)
+                   : launch_prefill<64, 8>(a, grid, stream);
+    } else {
+      e = d == 128 ? launch_prefill<128, 4>(a, grid, stream)
+                   : launch_prefill<64, 4>(a, grid, stream);
+    }
     if (e != hipSuccess) return e;
-    a.descs = static_cast<const SeqDesc*>(descs_dev);
-  }
-  hipError_t e;
-  if (split_keys) {
-    e = d == 128 ? launch_decode<128>(a, lp.n_slots, stream)
-                 : launch_decode<64>(a, lp.n_slots, stream);
-  } else if (lp.q_blocks == 2) {
-    e = d == 128 ? launch_prefill<128, 8>(a, lp.n_slots, stream)
-                 : launch_prefill<64, 8>(a, lp.n_slots, stream);
-  } else {
-    e = d == 128 ? launch_prefill<128, 4>(a, lp.n_slots, stream)
-                 : launch_prefill<64, 4>(a, lp.n_slots, stream);
-  }
-  if (e != hipSuccess || !lp.any_split) return e;
+    if (max_split == 1) continue;
 
-  MergeArgs m{};
-  m.part_o = a.part_o;
-  m.part_lse = a.part_lse;
-  m.out = a.out;
-  m.lse = a.lse;
-  m.descs = a.descs;
-  m.n_seq = a.n_seq;
-  m.h_q = a.h_q;
-  m.total_rows = lp.total_rows;
-  if (a.n_seq <= kMaxInlineSeq)
-    std::memcpy(m.inline_descs, lp.descs.data(), lp.descs.size() * sizeof(SeqDesc));
-  int max_split = 1;
-  for (const SeqDesc& sd : lp.descs) max_split = std::max(max_split, sd.n_split);
-  if (max_split > kWideMergeSplits) {
-    // many KV ranges per row: one workgroup per (row, head), ranges spread over its lanes
-    const int64_t blocks = (int64_t)lp.total_rows * a.h_q;
-    if (d == 128)
-      hipLaunchKernelGGL(split_merge_wide_kernel<128>, dim3((unsigned)blocks), dim3(kThreads), 0,
-                         stream, m);
-    else
-      hipLaunchKernelGGL(split_merge_wide_kernel<64>, dim3((unsigned)blocks), dim3(kThreads), 0,
-                         stream, m);
-    return hipGetLastError();
+    MergeArgs m{};
+    m.part_o = a.part_o;
+    m.part_lse = a.part_lse;
+    m.out = a.out;
+    m.lse = a.lse;
+    m.n_seq = n;
+    m.h_q = a.h_q;
+    m.total_rows = rank1 - rank0;
+    std::memcpy(m.inline_descs, a.inline_descs, n * sizeof(SeqDesc));
+    if (max_split > kWideMergeSplits) {
+      // many KV ranges per row: one workgroup per (row, head), ranges spread over its lanes
+      const int64_t blocks = (int64_t)m.total_rows * a.h_q;
+      if (d == 128)
+        hipLaunchKernelGGL(split_merge_wide_kernel<128>, dim3((unsigned)blocks), dim3(kThreads),
+                           0, stream, m);
+      else
+        hipLaunchKernelGGL(split_merge_wide_kernel<64>, dim3((unsigned)blocks), dim3(kThreads),
+                           0, stream, m);
+    } else {
+      const int64_t threads = (int64_t)m.total_rows * a.h_q * (d / 4);
+      const int grid_m = (int)ceil_div(threads, kThreads);
+      if (d == 128)
+        hipLaunchKernelGGL(split_merge_kernel<128>, dim3(grid_m), dim3(kThreads), 0, stream, m);
+      else
+        hipLaunchKernelGGL(split_merge_kernel<64>, dim3(grid_m), dim3(kThreads), 0, stream, m);
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  const int64_t threads = (int64_t)lp.total_rows * a.h_q * (d / 4);
-  const int grid = (int)ceil_div(threads, kThreads);
-  if (d == 128)
-    hipLaunchKernelGGL(split_merge_kernel<128>, dim3(grid), dim3(kThreads), 0, stream, m);
-  else
-    hipLaunchKernelGGL(split_merge_kernel<64>, dim3(grid), dim3(kThreads), 0, stream, m);
-  return hipGetLastError();
+  return hipSuccess;
 }
 
 int run_plan(const Plan& plan, const void* q, const medha_kv_cache* kv, const int32_t* page_table,
              int h_q, float softmax_scale, float* out, float* lse, void* workspace,
              size_t workspace_bytes, void* hip_stream) {
-  if (plan.bytes > 256 || plan.part_rows > 0) {
+  if (plan.part_rows > 0) {
     if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < plan.bytes)
       return MEDHA_ERR_WORKSPACE;
   }
@@ -133,12 +139,8 @@ int run_plan(const Plan& plan, const void* q, const medha_kv_cache* kv, const in
   a.h_kv = kv->num_kv_heads;
   a.scale_log2 = softmax_scale * kLog2e;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (launch_plan(plan.rows, false, kv->head_dim, a, ws ? ws + plan.off_descs_rows : nullptr,
-                  stream) != hipSuccess)
-    return MEDHA_ERR_HIP;
-  if (launch_plan(plan.keys, true, kv->head_dim, a, ws ? ws + plan.off_descs_keys : nullptr,
-                  stream) != hipSuccess)
-    return MEDHA_ERR_HIP;
+  if (launch_plan(plan.rows, false, kv->head_dim, a, stream) != hipSuccess) return MEDHA_ERR_HIP;
+  if (launch_plan(plan.keys, true, kv->head_dim, a, stream) != hipSuccess) return MEDHA_ERR_HIP;
   return MEDHA_OK;
 }
 
@@ -162,7 +164,7 @@ const char* medha_strerror(int code) {
   switch (code) {
     case MEDHA_OK: return "ok";
     case MEDHA_ERR_INVALID_ARG: return "invalid argument";
-    case MEDHA_ERR_UNSUPPORTED: return "unsupported shape (page size 16, head_dim 64 or 128, GQA group <= 32 for decode)";
+    case MEDHA_ERR_UNSUPPORTED: return "unsupported shape (page size must be 16, head_dim 64 or 128)";
     case MEDHA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case MEDHA_ERR_HIP: return "HIP runtime error";
     default: return "unknown error code";
@@ -224,7 +226,6 @@ size_t medha_decode_partial_workspace_bytes(const int32_t* kv_len, int32_t items
                                             int32_t head_dim) {
   if (items < 0 || (items > 0 && kv_len == nullptr)) return 0;
   if (check_heads(num_q_heads, num_kv_heads, head_dim, kPageSize) != MEDHA_OK) return 0;
-  if (num_q_heads / num_kv_heads > 32) return 0;
   std::vector<SeqInput> seqs(items);
   for (int i = 0; i < items; ++i) {
     if (kv_len[i] < 0) return 0;
@@ -243,7 +244,6 @@ int medha_decode_partial_attn(const void* q, int32_t num_queries, const medha_kv
   if (items < 0 || num_queries < 0) return MEDHA_ERR_INVALID_ARG;
   int rc = check_kv(kv, num_q_heads);
   if (rc != MEDHA_OK) return rc;
-  if (num_q_heads / kv->num_kv_heads > 32) return MEDHA_ERR_UNSUPPORTED;
   if (items == 0) return MEDHA_OK;
   if (q == nullptr || page_table == nullptr || page_table_offs == nullptr || q_index == nullptr ||
       kv_len == nullptr || out_partial == nullptr || lse_partial == nullptr)
@@ -453,30 +453,6 @@ int medha_kv_append(const void* k_new, const void* v_new, const medha_kv_cache* 
     if (hipGetLastError() != hipSuccess) return MEDHA_ERR_HIP;
   }
   return MEDHA_OK;
-}
-
-int medha_ceiling_mfma_bf16(const void* operands, size_t operand_bytes, int32_t blocks,
-                            int32_t iters, float* sink, size_t sink_floats, void* hip_stream) {
-  if (operands == nullptr || sink == nullptr || blocks <= 0 || iters <= 0)
-    return MEDHA_ERR_INVALID_ARG;
-  if (!aligned(operands, 16) || operand_bytes < 5 * 64 * 16) return MEDHA_ERR_INVALID_ARG;
-  if (sink_floats < (size_t)blocks * 512) return MEDHA_ERR_WORKSPACE;
-  hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(blocks), dim3(512), 0,
-                     static_cast<hipStream_t>(hip_stream),
-                     static_cast<const uint4*>(operands), iters, sink);
-  return hipGetLastError() == hipSuccess ? MEDHA_OK : MEDHA_ERR_HIP;
-}
-
-int medha_ceiling_stream_read(const void* src, size_t bytes, int32_t blocks, void* sink,
-                              size_t sink_bytes, void* hip_stream) {
-  if (src == nullptr || sink == nullptr || blocks <= 0 || bytes % 16 != 0)
-    return MEDHA_ERR_INVALID_ARG;
-  if (!aligned(src, 16) || !aligned(sink, 16)) return MEDHA_ERR_INVALID_ARG;
-  if (sink_bytes < (size_t)blocks * 256 * 16) return MEDHA_ERR_WORKSPACE;
-  hipLaunchKernelGGL(read_ceiling_kernel, dim3(blocks), dim3(256), 0,
-                     static_cast<hipStream_t>(hip_stream), static_cast<const u32x4*>(src),
-                     bytes / 16, static_cast<u32x4*>(sink));
-  return hipGetLastError() == hipSuccess ? MEDHA_OK : MEDHA_ERR_HIP;
 }
 
 // ------------------------------------------------------------------ policy (host only)

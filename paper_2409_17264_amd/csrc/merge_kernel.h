@@ -98,7 +98,7 @@ __global__ void __launch_bounds__(kThreads) lse_merge_kernel(
 template <int D>
 __global__ void __launch_bounds__(kThreads) split_merge_kernel(const MergeArgs args) {
   constexpr int per_row = D / 4;
-  const SeqDesc* descs = args.descs ? args.descs : args.inline_descs;
+  const SeqDesc* descs = args.inline_descs;
   const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   const int64_t total = (int64_t)args.total_rows * args.h_q * per_row;
   if (idx >= total) return;
@@ -131,7 +131,7 @@ __global__ void __launch_bounds__(kThreads) split_merge_wide_kernel(const MergeA
   constexpr int lanes = kThreads / per_row;
   __shared__ f32x4 sm_acc[lanes][per_row];
   __shared__ float sm_big[lanes], sm_wsum[lanes];
-  const SeqDesc* descs = args.descs ? args.descs : args.inline_descs;
+  const SeqDesc* descs = args.inline_descs;
   const int head = blockIdx.x % args.h_q;
   const int row = blockIdx.x / args.h_q;  // rank of the token row among the launch's rows
   int lo = 0, hi = args.n_seq - 1;

@@ -31,7 +31,7 @@ struct Plan {
   LaunchPlan keys;  // key-split mode: decodes and other tiny chunks
   int64_t part_rows = 0;  // token rows of split-KV partials (both launches)
   // workspace layout (byte offsets, 256-aligned)
-  size_t off_part_o = 0, off_part_lse = 0, off_descs_rows = 0, off_descs_keys = 0, bytes = 0;
+  size_t off_part_o = 0, off_part_lse = 0, bytes = 0;
 };
 
 struct SeqInput {
@@ -121,12 +121,6 @@ inline Plan make_plan(const SeqInput* seqs, int batch, int h_q, int h_kv, int he
   off = align256(off + (size_t)plan.part_rows * h_q * head_dim * sizeof(float));
   plan.off_part_lse = off;
   off = align256(off + (size_t)plan.part_rows * h_q * sizeof(float));
-  plan.off_descs_rows = off;
-  if ((int)plan.rows.descs.size() > kMaxInlineSeq)
-    off = align256(off + plan.rows.descs.size() * sizeof(SeqDesc));
-  plan.off_descs_keys = off;
-  if ((int)plan.keys.descs.size() > kMaxInlineSeq)
-    off = align256(off + plan.keys.descs.size() * sizeof(SeqDesc));
   plan.bytes = std::max<size_t>(off, 256);
   return plan;
 }

@@ -651,7 +651,7 @@ __global__ void __launch_bounds__(512) prefill_kernel(const AttnArgs args) {
   __shared__ __attribute__((aligned(1024))) char lds[Shape::kLdsBytes];
   const Ring stages{lds, lds_address(lds)};
 
-  const SeqDesc* descs = args.descs ? args.descs : args.inline_descs;
+  const SeqDesc* descs = args.inline_descs;
   const SeqDesc sd = uniform(descs[find_seq_slot(descs, args.n_seq, blockIdx.x)]);
 
   const SlotItem it =

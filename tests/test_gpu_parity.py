@@ -69,8 +69,11 @@ def test_ragged_batch_mixed_modes():
 
 
 # ------------------------------------------------------------------ decode
-@pytest.mark.parametrize("h_q,h_kv,d", [(32, 8, 128), (8, 1, 128), (2, 1, 64), (4, 4, 64)])
+@pytest.mark.parametrize("h_q,h_kv,d", [(32, 8, 128), (8, 1, 128), (2, 1, 64), (4, 4, 64),
+                                        (64, 1, 128), (48, 1, 64)])
 def test_decode_partial_lengths(h_q, h_kv, d):
+    """Lengths from empty to 20000 keys; groups of more than 32 query heads per KV head take
+    the row-split kernel instead of the key-split one."""
     lens = np.array([0, 1, 15, 16, 17, 127, 128, 129, 511, 1000, 5000, 20000], np.int32)
     items = len(lens)
     need = [wl.pages_for(int(n)) for n in lens]
@@ -257,6 +260,91 @@ def test_invalid_arguments_are_rejected_without_writing():
     assert e.value.code == -3
     torch.cuda.synchronize()
     assert bool((out == 7.0).all()) and bool((lse == 7.0).all())
+
+
+def test_other_entry_points_reject_bad_arguments_without_writing():
+    """Every validation failure of the decode-partial, chunk-partial, merge and append entry
+    points returns its code with nothing enqueued: sentinel-filled outputs and pools stay
+    as they were."""
+    b = to_dev(wl.make_prefill_batch("e2", 8, 2, 128, [100], [20], seed=3))
+    pt = torch.from_numpy(b.page_table).cuda()
+    offs = b.page_table_offs
+    out = torch.full((20, 8, 128), 7.0, device="cuda")
+    lse = torch.full((20, 8), 7.0, device="cuda")
+    k_before, v_before = b.k_pool.clone(), b.v_pool.clone()
+
+    def expect(code, fn, *a, **kw):
+        with pytest.raises(medha.MedhaError) as e:
+            fn(*a, **kw)
+        assert e.value.code == code, (fn.__name__, e.value.code)
+
+    q1 = b.q[:2].contiguous()
+    o1, l1 = out[:1], lse[:1]
+    dec = medha.decode_partial_attn
+    expect(-1, dec, q1, b.k_pool, b.v_pool, pt, offs, [0], [-1], b.scale, o1, l1)    # kv_len < 0
+    expect(-1, dec, q1, b.k_pool, b.v_pool, pt, offs, [2], [50], b.scale, o1, l1)    # q_index
+    expect(-1, dec, q1, b.k_pool, b.v_pool, pt, offs, [0], [500], b.scale, o1, l1)   # table short
+    expect(-1, dec, q1, b.k_pool, b.v_pool, pt, [3, 1], [0], [10], b.scale, o1, l1)  # offsets
+    expect(-1, dec, q1, b.k_pool, b.v_pool, pt, offs, [0], [50], float("nan"), o1, l1)
+    k32 = b.k_pool[..., :32].contiguous()
+    expect(-2, dec, q1[..., :32].contiguous(), k32, k32, pt, offs, [0], [50], b.scale)
+    long = to_dev(wl.make_prefill_batch("e3", 8, 2, 128, [99999], [1], seed=4))
+    assert medha.decode_partial_workspace_bytes([100000], 8, 2, 128) > 256
+    expect(-3, dec, long.q, long.k_pool, long.v_pool, torch.from_numpy(long.page_table).cuda(),
+           long.page_table_offs, [0], [100000], long.scale, o1, l1,
+           workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+
+    chk = medha.chunk_partial_attn
+    for q_row, c, n, vis, code in (([1], [20], [120], [101], -1), ([0], [0], [120], [101], -1),
+                                   ([0], [20], [-1], [101], -1), ([0], [20], [1000], [101], -1),
+                                   ([0], [20], [120], [(1 << 30) + 1], -1)):
+        rows = int(sum(c))
+        expect(code, chk, b.q, b.k_pool, b.v_pool, pt, offs, q_row, c, n, vis, b.scale,
+               out[:rows], lse[:rows])
+
+    po = torch.ones((3, 20, 8, 128), device="cuda")
+    pl = torch.ones((3, 20, 8), device="cuda")
+    lib = medha.load_library()
+    dp = lambda t: t.data_ptr()
+    stream = torch.cuda.current_stream().cuda_stream
+    assert lib.medha_lse_merge(dp(po), dp(pl), 0, 20, 8, 128, dp(out), dp(lse), stream) == -1
+    assert lib.medha_lse_merge(dp(po), dp(pl), 3, -1, 8, 128, dp(out), dp(lse), stream) == -1
+    assert lib.medha_lse_merge(dp(po), dp(pl), 3, 20, 8, 126, dp(out), dp(lse), stream) == -2
+    assert lib.medha_lse_merge(dp(po) + 4, dp(pl), 3, 20, 8, 128, dp(out), dp(lse), stream) == -1
+    assert lib.medha_lse_merge(dp(po), dp(pl), 3, 20, 8, 128, None, dp(lse), stream) == -1
+
+    k_new = torch.ones((20, 2, 128), dtype=torch.bfloat16, device="cuda")
+    app = medha.kv_append
+    expect(-1, app, k_new, k_new, b.k_pool, b.v_pool, pt, offs, [-1], [20])          # prefix < 0
+    expect(-1, app, k_new[:0], k_new[:0], b.k_pool, b.v_pool, pt, offs, [100], [0])  # empty chunk
+    expect(-1, app, k_new, k_new, b.k_pool, b.v_pool, pt, [0, 3], [100], [20])       # table short
+    k40 = torch.ones((40, 2, 128), dtype=torch.bfloat16, device="cuda")
+    # the second sequence is the bad one: nothing of the first may be written either
+    expect(-1, app, k40, k40, b.k_pool, b.v_pool, pt, [0, 8, 8], [100, 0], [20, 20])
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all()) and bool((lse == 7.0).all())
+    assert torch.equal(b.k_pool.view(torch.int16), k_before.view(torch.int16))
+    assert torch.equal(b.v_pool.view(torch.int16), v_before.view(torch.int16))
+
+
+@pytest.mark.parametrize("n_seq,h_q,h_kv,d", [(150, 8, 2, 128), (200, 4, 4, 64)])
+def test_batches_of_more_than_64_sequences_per_kernel(n_seq, h_q, h_kv, d):
+    """More than 64 sequences in BOTH kernels of one call (descriptors travel in the kernel
+    arguments, 64 per launch): every third sequence is a multi-row chunk, some long enough to be
+    KV-split and merged, the others decodes of assorted lengths."""
+    rng = np.random.default_rng(n_seq)
+    chunk = np.where(np.arange(n_seq) % 3 == 0, rng.integers(9, 60, n_seq), 1).astype(np.int32)
+    prefix = rng.integers(0, 700, n_seq).astype(np.int32)
+    prefix[::29] += 6000
+    b = wl.make_prefill_batch("many", h_q, h_kv, d, prefix, chunk, seed=n_seq, poison_unused=True)
+    e, gr, gk, _ = medha.describe_plan(b.prefix_len, b.chunk_len, h_q, h_kv, d)
+    assert sum(x.mode == 0 for x in e) > 0 and sum(x.mode == 1 for x in e) > 64
+    if h_q // h_kv * 9 > 32:
+        assert sum(x.mode == 0 for x in e) > 0
+    ro, rl = oracle_prefill(b)
+    b = to_dev(b)
+    out, lse = gpu_prefill(b)
+    check(out, lse, ro, rl, f"{n_seq} sequences hq{h_q} hkv{h_kv} d{d}")
 
 
 # ------------------------------------------------------------------- KV append

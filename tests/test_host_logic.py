@@ -7,22 +7,29 @@ import numpy as np
 import pytest
 
 import paper_2409_17264_amd as medha
-from paper_2409_17264_amd import binding, policy
+from paper_2409_17264_amd import binding, policy, yardstick
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    declared = set()
+    declared = {}
     for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
         header = open(os.path.join(ROOT, "include", name)).read()
         body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)      # drop comments
-        declared |= set(re.findall(r"\b(medha_[a-z0-9_]+)\s*\(", body))
+        declared[name] = set(re.findall(r"\b(medha_[a-z0-9_]+)\s*\(", body))
+    assert sorted(declared) == ["medha.h", "medha_policy.h", "medha_yardstick.h"]
+    product = declared["medha.h"] | declared["medha_policy.h"]
     bound = set(binding.EXPORTS) | set(policy.EXPORTS)
-    assert declared == bound, declared ^ bound
+    assert product == bound, product ^ bound
+    assert declared["medha_yardstick.h"] == set(yardstick.EXPORTS)
     lib = medha.load_library()
-    for name in declared:
+    for name in product:
         assert getattr(lib, name) is not None
+    ylib = yardstick.load_library()
+    for name in yardstick.EXPORTS:
+        assert getattr(ylib, name) is not None
+        assert not hasattr(lib, name)          # the yardsticks are not in the product's ABI
     assert lib.medha_abi_version() == 1
     assert lib.medha_strerror(0) == b"ok"
     assert b"workspace" in lib.medha_strerror(-3)
@@ -33,7 +40,7 @@ def test_workspace_queries_reject_bad_arguments():
     assert medha.chunked_prefill_workspace_bytes([10], [4], 7, 2, 128) == 0       # 7 % 2
     assert medha.chunked_prefill_workspace_bytes([10], [4], 8, 2, 96) == 0        # head_dim
     assert medha.decode_partial_workspace_bytes([-1], 8, 2, 128) == 0
-    assert medha.decode_partial_workspace_bytes([5], 64, 1, 128) == 0             # group > 32
+    assert medha.decode_partial_workspace_bytes([5], 64, 1, 128) >= 256           # group > 32: row-split
     assert medha.chunked_prefill_workspace_bytes([100], [16], 8, 2, 128) >= 256
 
 
