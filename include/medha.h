@@ -109,6 +109,29 @@ size_t medha_chunked_prefill_workspace_bytes(const int32_t* prefix_len, const in
                                              int32_t num_kv_heads, int32_t head_dim);
 
 /*
+ * medha_chunked_prefill_attn for callers that cannot allocate device memory or hand
+ * over a workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and error codes, without the workspace:
+ * the split-KV partials go to a scratch array of MEDHA_NOALLOC_SCRATCH_BYTES that is
+ * part of the library's device image (every GPU the library runs on holds its own copy
+ * until the process ends).  The call allocates nothing and calls no allocating routine;
+ * its first call on a device looks the array's address up (make that call outside a
+ * graph capture).  A batch whose workspace need, as reported by
+ * medha_chunked_prefill_workspace_bytes, exceeds MEDHA_NOALLOC_SCRATCH_BYTES is
+ * refused with MEDHA_ERR_WORKSPACE and nothing is enqueued.  All calls on one GPU share
+ * that GPU's array: calls that overlap on one GPU (different streams, or graphs
+ * replayed concurrently) race on it and must be serialised by the caller.  Nothing in
+ * the array has to start at zero: every partial is written before it is read.
+ */
+#define MEDHA_NOALLOC_SCRATCH_BYTES (64u << 20)
+int medha_chunked_prefill_attn_noalloc(const void* q, const medha_kv_cache* kv,
+                                       const int32_t* page_table,
+                                       const int64_t* page_table_offs, const int32_t* prefix_len,
+                                       const int32_t* chunk_len, int32_t batch,
+                                       int32_t num_q_heads, float softmax_scale, float* out,
+                                       float* lse, void* hip_stream);
+
+/*
  * Split-KV decode partial (paper section 3.3 "Bounding Decode Latency": the
  * query is replicated to every KV shard, each computes a partial attention
  * output over its local keys).  Item i takes query token q_index[i] and

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     chunk_partial_attn,
     chunk_partial_workspace_bytes,
     chunked_prefill_attn,
+    chunked_prefill_attn_noalloc,
     chunked_prefill_workspace_bytes,
     decode_partial_attn,
     decode_partial_workspace_bytes,

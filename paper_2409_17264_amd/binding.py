@@ -20,6 +20,7 @@ _LIB = None
 EXPORTS = (
     "medha_chunked_prefill_attn",
     "medha_chunked_prefill_workspace_bytes",
+    "medha_chunked_prefill_attn_noalloc",
     "medha_decode_partial_attn",
     "medha_decode_partial_workspace_bytes",
     "medha_chunk_partial_attn",
@@ -75,6 +76,9 @@ def load_library():
     lib.medha_decode_partial_attn.restype = ctypes.c_int
     lib.medha_decode_partial_attn.argtypes = [vp, i32, ctypes.POINTER(_KvCache), vp, vp, vp, vp,
                                               i32, i32, f32, vp, vp, vp, sz, vp]
+    lib.medha_chunked_prefill_attn_noalloc.restype = ctypes.c_int
+    lib.medha_chunked_prefill_attn_noalloc.argtypes = [vp, ctypes.POINTER(_KvCache), vp, vp, vp,
+                                                       vp, i32, i32, f32, vp, vp, vp]
     lib.medha_decode_partial_workspace_bytes.restype = sz
     lib.medha_decode_partial_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
     lib.medha_chunk_partial_attn.restype = ctypes.c_int
@@ -201,6 +205,32 @@ def chunked_prefill_attn(q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Te
     _check(lib.medha_chunked_prefill_attn(
         _dp(q), ctypes.byref(kv), _dp(page_table), _hp(offs), _hp(pre), _hp(chk), batch, h_q,
         float(softmax_scale), _dp(out), _dp(lse), _dp(workspace), workspace.numel(), _stream()))
+    return out, lse
+
+
+NOALLOC_SCRATCH_BYTES = 64 << 20
+
+
+def chunked_prefill_attn_noalloc(q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor,
+                                 page_table: torch.Tensor, page_table_offs, prefix_len, chunk_len,
+                                 softmax_scale: float, out: torch.Tensor, lse: torch.Tensor):
+    """chunked_prefill_attn through the entry point that allocates nothing: the caller passes
+    every tensor, the split-KV partials go to the library's own scratch array."""
+    lib = load_library()
+    assert q.is_cuda and q.dtype == torch.bfloat16 and q.is_contiguous() and q.dim() == 3
+    assert page_table.is_cuda and page_table.dtype == torch.int32 and page_table.is_contiguous()
+    tokens, h_q, d = q.shape
+    kv = _kv(k_pool, v_pool)
+    offs = _host(page_table_offs, np.int64)
+    pre, chk = _host(prefix_len, np.int32), _host(chunk_len, np.int32)
+    batch = len(pre)
+    assert len(chk) == batch and len(offs) == batch + 1 and int(chk.sum()) == tokens
+    assert int(offs[-1]) <= page_table.numel()
+    assert out.dtype == torch.float32 and out.is_contiguous() and out.shape == (tokens, h_q, d)
+    assert lse.dtype == torch.float32 and lse.is_contiguous() and lse.shape == (tokens, h_q)
+    _check(lib.medha_chunked_prefill_attn_noalloc(
+        _dp(q), ctypes.byref(kv), _dp(page_table), _hp(offs), _hp(pre), _hp(chk), batch, h_q,
+        float(softmax_scale), _dp(out), _dp(lse), _stream()))
     return out, lse
 
 

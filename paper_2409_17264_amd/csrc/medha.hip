@@ -6,6 +6,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "append_kernel.h"
@@ -16,8 +17,38 @@
 #include "policy.h"
 #include "prefill_kernel.h"
 
+// Scratch of medha_chunked_prefill_attn_noalloc: split-KV partials of one call.  Every GPU
+// the library runs on holds its own copy, at its own address, until the process ends.  In
+// host code this name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[MEDHA_NOALLOC_SCRATCH_BYTES];
+
 namespace medha {
 namespace {
+
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+void* noalloc_scratch_ptr(int* rc) {
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    *rc = MEDHA_ERR_HIP;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      *rc = MEDHA_ERR_HIP;
+      return nullptr;
+    }
+    ptr[dev] = p;
+  }
+  *rc = MEDHA_OK;
+  return ptr[dev];
+}
 
 int current_num_cus() {
   int dev = 0, cus = 0;
@@ -219,6 +250,27 @@ int medha_chunked_prefill_attn(const void* q, const medha_kv_cache* kv, const in
                               current_num_cus());
   return run_plan(plan, q, kv, page_table, num_q_heads, softmax_scale, out, lse, workspace,
                   workspace_bytes, hip_stream);
+}
+
+int medha_chunked_prefill_attn_noalloc(const void* q, const medha_kv_cache* kv,
+                                       const int32_t* page_table,
+                                       const int64_t* page_table_offs, const int32_t* prefix_len,
+                                       const int32_t* chunk_len, int32_t batch,
+                                       int32_t num_q_heads, float softmax_scale, float* out,
+                                       float* lse, void* hip_stream) {
+  // The size check comes first so that an oversized batch is refused whatever else is wrong
+  // with it; medha_chunked_prefill_attn validates everything again.
+  if (batch > 0 && kv != nullptr && prefix_len != nullptr && chunk_len != nullptr) {
+    const size_t need = medha_chunked_prefill_workspace_bytes(
+        prefix_len, chunk_len, batch, num_q_heads, kv->num_kv_heads, kv->head_dim);
+    if (need > (size_t)MEDHA_NOALLOC_SCRATCH_BYTES) return MEDHA_ERR_WORKSPACE;
+  }
+  int rc = MEDHA_OK;
+  void* ws = noalloc_scratch_ptr(&rc);
+  if (rc != MEDHA_OK) return rc;
+  return medha_chunked_prefill_attn(q, kv, page_table, page_table_offs, prefix_len, chunk_len,
+                                    batch, num_q_heads, softmax_scale, out, lse, ws,
+                                    (size_t)MEDHA_NOALLOC_SCRATCH_BYTES, hip_stream);
 }
 
 size_t medha_decode_partial_workspace_bytes(const int32_t* kv_len, int32_t items,
