@@ -34,8 +34,9 @@ typedef struct medha_time_model {
   double t_decode_key;
 } medha_time_model;
 
-/* Predicted time of one chunk (see above).  NaN for a null or invalid model or
- * negative sizes. */
+/* Predicted time of one chunk (see above).  Sizes are limited to kv_size <= 2^40 and
+ * chunk <= 2^24 in every call of this header (the pair count stays exact in fp64).
+ * NaN for a null or invalid model or sizes outside that range. */
 double medha_policy_chunk_time(const medha_time_model* model, int64_t kv_size, int64_t chunk);
 
 /* Least-squares fit, in relative error (sum of ((predicted - measured) / measured)^2),
@@ -48,8 +49,9 @@ int medha_policy_fit_time_model(const int64_t* kv_size, const int64_t* chunk,
                                 const double* seconds, int32_t n, medha_time_model* model,
                                 double* max_rel_err);
 
-/* The binary search of Algorithm 2 (appendix "Adaptive Chunk Size Selection"):
- * the largest c in [0, max_chunk] whose predicted chunk time is <= t_budget.
+/* The chunk search of Algorithm 2 (appendix "Adaptive Chunk Size Selection"):
+ * the largest c in [0, max_chunk] whose predicted chunk time is <= t_budget
+ * (the time is a quadratic in c: closed form, corrected by exact evaluation).
  * Returns -1 for bad arguments. */
 int64_t medha_policy_max_chunk(const medha_time_model* model, int64_t kv_size, double t_budget,
                                int64_t max_chunk);

@@ -438,8 +438,10 @@ int medha_lse_merge(const float* out_partial, const float* lse_partial, int32_t 
   if (out_partial == nullptr || lse_partial == nullptr || out == nullptr || lse == nullptr)
     return MEDHA_ERR_INVALID_ARG;
   if (!aligned(out_partial, 16) || !aligned(out, 16)) return MEDHA_ERR_INVALID_ARG;
-  const int64_t threads = rows * num_q_heads * (head_dim / 4);
-  const int64_t grid = ceil_div(threads, kThreads);
+  // one thread per 4 output elements; the grid has to fit 31 bits (checked without overflow)
+  const int64_t per_row = (int64_t)num_q_heads * (head_dim / 4);
+  if (rows > ((int64_t)INT32_MAX * kThreads) / per_row) return MEDHA_ERR_INVALID_ARG;
+  const int64_t grid = ceil_div(rows * per_row, kThreads);
   if (grid > INT32_MAX) return MEDHA_ERR_INVALID_ARG;
   hipLaunchKernelGGL(lse_merge_kernel, dim3((unsigned)grid), dim3(kThreads), 0,
                      static_cast<hipStream_t>(hip_stream), out_partial, lse_partial, num_splits,
@@ -509,7 +511,8 @@ int medha_kv_append(const void* k_new, const void* v_new, const medha_kv_cache* 
 
 // ------------------------------------------------------------------ policy (host only)
 double medha_policy_chunk_time(const medha_time_model* model, int64_t kv_size, int64_t chunk) {
-  if (!policy::valid(model) || kv_size < 0 || chunk < 0)
+  if (!policy::valid(model) || kv_size < 0 || chunk < 0 || kv_size > (1ll << 40) ||
+      chunk > (1 << 24))
     return std::numeric_limits<double>::quiet_NaN();
   return policy::chunk_time(*model, kv_size, chunk);
 }
@@ -523,9 +526,11 @@ int medha_policy_fit_time_model(const int64_t* kv_size, const int64_t* chunk,
   for (int i = 0; i < n; ++i) {
     if (kv_size[i] < 0 || chunk[i] < 1 || !(seconds[i] > 0.0) || !std::isfinite(seconds[i]))
       return -1;
+    if (kv_size[i] > (1ll << 40) || chunk[i] > (1 << 24)) return -1;
     x[0].push_back(1.0);
     x[1].push_back((double)chunk[i]);
-    x[2].push_back((double)(chunk[i] * kv_size[i]) + (double)(chunk[i] * (chunk[i] + 1)) / 2.0);
+    x[2].push_back((double)chunk[i] * (double)kv_size[i] +
+                   (double)(chunk[i] * (chunk[i] + 1)) / 2.0);
   }
   // all three columns first; drop a column whose coefficient comes out negative and refit
   bool use[3] = {true, true, true};
@@ -572,12 +577,14 @@ int64_t medha_policy_get_chunk_size(const medha_time_model* model, int64_t kv_si
   if (std::isnan(rel_slack) || !(rho_max >= 0.0 && rho_max <= 1.0) || std::isnan(t_current) ||
       !(t_target >= 0.0))
     return -1;
+  // one long prefill per batch; otherwise the iteration's time budget, shrunk in proportion
+  // to the slack the request can afford to give away (at most rho_max of it), less what the
+  // batch already costs
   if (is_long && batch_has_long) return 0;
-  const double rho = std::min(rho_max, std::max(0.0, rel_slack));
-  const double t_effective = t_target * (1.0 - rho);
-  const double t_budget = t_effective - t_current;
-  if (t_budget <= 0.0) return 0;
-  return policy::max_chunk(*model, kv_size, t_budget, std::min(max_chunk, remaining));
+  const double yielded = rel_slack > 0.0 ? (rel_slack < rho_max ? rel_slack : rho_max) : 0.0;
+  const double left = t_target * (1.0 - yielded) - t_current;
+  if (!(left > 0.0)) return 0;
+  return policy::max_chunk(*model, kv_size, left, max_chunk < remaining ? max_chunk : remaining);
 }
 
 double medha_policy_simulate_prefill(const medha_time_model* model, int64_t length,

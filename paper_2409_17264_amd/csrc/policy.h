@@ -21,35 +21,53 @@ inline bool valid(const medha_time_model* m) {
   return true;
 }
 
-// t_token * c + t_pair * (c * kv + c (c + 1) / 2); sizes stay below 2^53 in the products
+// t_token * c + t_pair * (c * kv + c (c + 1) / 2), for kv <= 2^40 and c <= 2^24 (the callers
+// check): c * kv can pass 2^63, so that product is taken in floating point (both factors are
+// exact there and the product is correctly rounded); c (c + 1) stays below 2^49.
 inline double chunk_time(const medha_time_model& m, int64_t kv, int64_t c) {
-  const double pairs = (double)(c * kv) + (double)(c * (c + 1)) / 2.0;
+  const double pairs = (double)c * (double)kv + (double)(c * (c + 1)) / 2.0;
   return m.t_token * (double)c + m.t_pair * pairs;
 }
 
-// Largest c in [0, hi] with chunk_time(kv, c) <= budget (the time grows with c).
+// Largest c in [0, hi] with chunk_time(kv, c) <= budget.  The time is a quadratic in c,
+//     (t_pair / 2) c^2 + (t_token + t_pair (kv + 1/2)) c,
+// so the answer is the floor of its positive root at `budget`, taken in closed form and then
+// walked by the one or two steps the rounding of the root may be off, with chunk_time itself
+// as the judge (it grows with c, so the walk ends at the exact answer).
 inline int64_t max_chunk(const medha_time_model& m, int64_t kv, double budget, int64_t hi) {
-  int64_t lo = 0;  // always fits when budget >= 0 ... checked by the caller for c >= 1 below
-  if (hi < 1 || !(chunk_time(m, kv, 1) <= budget)) return 0;
-  lo = 1;
-  while (lo < hi) {
-    const int64_t mid = lo + (hi - lo + 1) / 2;
-    if (chunk_time(m, kv, mid) <= budget) lo = mid; else hi = mid - 1;
+  if (hi < 1 || !(budget >= 0.0)) return 0;
+  const double a = 0.5 * m.t_pair;
+  const double b = m.t_token + m.t_pair * ((double)kv + 0.5);
+  double root;
+  if (a > 0.0) {
+    // the form without cancellation: 2 budget / (b + sqrt(b^2 + 4 a budget))
+    root = 2.0 * budget / (b + std::sqrt(b * b + 4.0 * a * budget));
+  } else if (b > 0.0) {
+    root = budget / b;
+  } else {
+    root = (double)hi;  // every chunk is free
   }
-  return lo;
+  int64_t c = root >= (double)hi ? hi : (root > 0.0 ? (int64_t)root : 0);
+  while (c < hi && chunk_time(m, kv, c + 1) <= budget) ++c;
+  while (c > 0 && !(chunk_time(m, kv, c) <= budget)) --c;
+  return c;
 }
 
+// Time of a whole prefill of `length` tokens when every iteration takes the largest chunk
+// that fits t_target (Algorithm 3's estimate): a walk over chunk boundaries.  A position
+// where not even one token fits ends the estimate there.
 inline double simulate_prefill(const medha_time_model& m, int64_t length, double t_target,
                                int64_t max_c) {
-  double total = 0.0;
-  int64_t done = 0;
-  while (done < length) {
-    const int64_t c = max_chunk(m, done, t_target - m.t_fixed, std::min(max_c, length - done));
+  const double per_iteration = t_target - m.t_fixed;  // what is left for the chunk itself
+  double elapsed = 0.0;
+  for (int64_t pos = 0; pos < length;) {
+    const int64_t room = length - pos;
+    const int64_t c = max_chunk(m, pos, per_iteration, room < max_c ? room : max_c);
     if (c == 0) break;
-    total += m.t_fixed + chunk_time(m, done, c);
-    done += c;
+    elapsed += m.t_fixed + chunk_time(m, pos, c);
+    pos += c;
   }
-  return total;
+  return elapsed;
 }
 
 // Solves the k x k system a x = b in place (partial pivoting); false if singular.
