@@ -461,6 +461,13 @@ struct RowBlock {
 
     auto slot = [&](auto slot_index) {
       constexpr int i = decltype(slot_index)::value;
+      // The wavefront's issue priority falls as it advances through the tile (3, 2, 1, 0 by
+      // quarters).  Two wavefronts share a SIMD and meet at a barrier after every tile; with
+      // equal priorities the arbiter serves the older one first, which then finishes its
+      // tile early and idles at the barrier (measured: a quarter of its time) while the
+      // other runs on alone -- and one wavefront alone cannot keep the matrix pipe full.
+      // This way whichever is behind wins the arbitration and both arrive together.
+      if constexpr (i % (kSlots / 4) == 0) __builtin_amdgcn_s_setprio(3 - i / (kSlots / 4));
       read_operand(i + 3);
       if constexpr (i < kQk) {
         if constexpr (QK)
@@ -490,7 +497,8 @@ struct RowBlock {
         for (int e = 0; e < 8; ++e)
           if ((e * kSpan) / 8 == r) {
             const float pe = prob<MASK>(sc[g >> 1][8 * (g & 1) + e], m_use);
-            ls += pe;
+            // (the first term after a check starts the sum: no addition to zero)
+            if (kSpec && (g & 1) == 0 && e == 0) ls = pe; else ls += pe;
             if (e & 1) {
               const f32x2 pair = {pe_prev, pe};
               pw[g][e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pair, bf16x2));
@@ -517,7 +525,7 @@ struct RowBlock {
       __builtin_amdgcn_sched_barrier(0);
     };
     static_for<kSlots>(slot);
-    add_to_sum(ls);
+    if (!kSpec) add_to_sum(ls);  // (the speculative route adds at its checks)
   }
 };
 
