@@ -201,6 +201,9 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--sections", default="ceilings,main,append,decode,sweep,policy,mixed,cpu")
+    ap.add_argument("--chunks", default="32,128,512,1024,2048,4096,8192",
+                    help="chunk lengths of the sweep section (the policy fit needs at least "
+                         "three of 512 and above)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (KV-cache parallelism is exercised "
@@ -349,7 +352,8 @@ def main():
     if "sweep" in sections:
         sweep = []
         base = wl.config4_llama70b_tp(8192, "cuda:0")
-        for chunk in (32, 128, 512, 1024, 2048, 4096, 8192):
+        chunks = [int(c) for c in args.chunks.split(",")]
+        for chunk in chunks:
             bb = wl.PrefillBatch(f"cfg4_c{chunk}", base.h_q, base.h_kv, base.d, base.prefix_len,
                                  np.array([chunk], np.int32), base.page_table,
                                  base.page_table_offs, base.num_pages,
@@ -369,12 +373,12 @@ def main():
                                                f"prefill_kernel_cfg4_c{chunk}_pmc.txt")})
         per_tok = {p["chunk"]: p["us_per_token"] for p in sweep}
         result["sweep"] = {"workload": "cfg4 Llama-3-70B TP8 share: 8 q / 1 kv head, d 128, "
-                                       "prefix 1,048,576", "points": sweep,
-                           # the paper's measure of how flat attention cost per token stays as
-                           # chunks shrink (section 3.1 "Empirical Validation" quotes 11 % on its
-                           # own hardware and kernels)
-                           "overhead_32_vs_2048_percent":
-                               100.0 * (per_tok[32] / per_tok[2048] - 1.0)}
+                                       "prefix 1,048,576", "points": sweep}
+        if 32 in per_tok and 2048 in per_tok:
+            # the paper's measure of how flat attention cost per token stays as chunks shrink
+            # (section 3.1 "Empirical Validation" quotes 11 % on its own hardware and kernels)
+            result["sweep"]["overhead_32_vs_2048_percent"] = \
+                100.0 * (per_tok[32] / per_tok[2048] - 1.0)
         del bb, run
         # KV-cache parallelism for the chunk: what ONE GPU of a KVP group of S does -- the
         # chunk against its shard of the 1M-token cache (here the last, causal shard) -- and
@@ -382,9 +386,10 @@ def main():
         chunk = 2048
         n = int(base.prefix_len[0]) + chunk
         pt_dev = torch.from_numpy(base.page_table).cuda()
+        kvp_degrees = (1, 2, 4, 8) if len(chunks) > 3 else ()
         qc = base.q[:chunk].contiguous()
         kvp = []
-        for shards in (1, 2, 4, 8):
+        for shards in kvp_degrees:
             per = ((n + shards - 1) // shards + 15) // 16 * 16
             lo = (shards - 1) * per
             offs = np.array([lo // 16, lo // 16 + (n - lo + 15) // 16], np.int64)
@@ -414,7 +419,7 @@ def main():
                             "hbm", merge_bytes / (tm["event_ms_mean"] * 1e-3) / 1e9,
                             "lse_merge_kernel", tm)})
             del po, pl, ws, allo, alll, mo, ml
-        if "policy" in sections:
+        if "policy" in sections and len([p for p in sweep if p["chunk"] >= 512]) >= 3:
             # the scheduling helpers on THIS device's timings: fit the runtime model to the sweep
             # plus a few shorter prefixes, then ask the paper's policy what it would do
             from paper_2409_17264_amd import policy as pol

@@ -23,6 +23,7 @@ constexpr int kWaves = 4;
 constexpr int kXcds = 8;          // accelerator dies; workgroup i is dispatched to die i % 8
 constexpr int kPrefillStages = 4;  // K/V tiles in flight per workgroup (LDS ring)
 constexpr int kMaxInlineSeq = 64; // sequence descriptors per kernel launch (they travel as kernel arguments)
+constexpr int kShortWalkTiles = 24;   // key-split launches walking at most this many 128-key tiles per workgroup use the small ring
 constexpr int kWideMergeSplits = 16;  // more KV ranges per row than this: the wide merge kernel
 constexpr float kRescaleSlack = 8.f;  // log2 units a row maximum may exceed the softmax reference
 constexpr float kLog2e = 1.4426950408889634f;

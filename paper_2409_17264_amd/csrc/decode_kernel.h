@@ -24,7 +24,7 @@
 
 namespace medha {
 
-template <int D>
+template <int D, int STAGES = 2>
 struct DecodeGeom {
   static constexpr int kBlockKeys = 32;
   static constexpr int kChunksPerRow = D / 8;
@@ -33,7 +33,7 @@ struct DecodeGeom {
   static constexpr int kHalfBytes = kBlockKeys * D * 2;                // K (or V) block
   static constexpr int kBlockBytes = 2 * kHalfBytes;
   static constexpr int kLoadsPerBlock = 2 * kInstrPerBlock;
-  static constexpr int kStagesPerWave = 2;
+  static constexpr int kStagesPerWave = STAGES;
   static constexpr int kLdsBytes = kWaves * kStagesPerWave * kBlockBytes;
   static constexpr int kSplitKeys = kBlockKeys * kWaves;  // planner's KV-split granule (128)
 };
@@ -69,13 +69,17 @@ __device__ __forceinline__ void issue_block(const AttnArgs& args, int page0, int
   }
 }
 
-template <int D>
+// STAGES = blocks in flight per wavefront.  2 (128 KiB of LDS, one workgroup per compute unit)
+// suits long walks; 1 (64 KiB, two workgroups per compute unit, so that one's start-up --
+// descriptor, page ids, the first blocks' trip to HBM -- and its final combine hide behind
+// the other's stream) suits launches whose workgroups walk only a few blocks each.
 // (launched with 256 threads; the bound of 512 makes the compiler budget for two wavefronts
 // per SIMD, i.e. at most 256 vector registers, all architectural: with more it parks the
 // accumulators in AGPRs and copies them back and forth around every vector-ALU use)
+template <int D, int STAGES>
 __global__ void __launch_bounds__(2 * kThreads)
 decode_kernel(const AttnArgs args) {
-  using G = DecodeGeom<D>;
+  using G = DecodeGeom<D, STAGES>;
   __shared__ __attribute__((aligned(1024))) char lds[G::kLdsBytes];
 
   const SeqDesc* descs = args.inline_descs;
@@ -138,17 +142,17 @@ decode_kernel(const AttnArgs args) {
   auto run_blocks = [&](int b0, int b_end, auto mask_tag) {
     constexpr bool MASK = decltype(mask_tag)::value;
     if (b0 < b_end) issue(b0, 0);
-    if (b0 + kWaves < b_end) issue(b0 + kWaves, 1);
+    if (STAGES == 2 && b0 + kWaves < b_end) issue(b0 + kWaves, 1);
     int st = 0;
-    for (int b = b0; b < b_end; b += kWaves, st ^= 1) {
-      if (b + kWaves < b_end)
+    for (int b = b0; b < b_end; b += kWaves, st ^= (STAGES - 1)) {
+      if (STAGES == 2 && b + kWaves < b_end)
         wait_vmcnt<G::kLoadsPerBlock>();  // the younger block may still fly
       else
         wait_vmcnt<0>();
       const char* base = ring + st * G::kBlockBytes;
       rb.template step<1, MASK>(base, base + G::kHalfBytes, k_begin + b * G::kBlockKeys, half);
       // every LDS read of the stage has returned (its data fed the matrix cores)
-      if (b + 2 * kWaves < b_end) issue(b + 2 * kWaves, st);
+      if (b + STAGES * kWaves < b_end) issue(b + STAGES * kWaves, st);
     }
   };
   // blocks below n_unmasked are visible to every row; this wavefront's first block at or
@@ -165,52 +169,62 @@ decode_kernel(const AttnArgs args) {
   const int64_t row_base =
       direct ? (int64_t)sd.out_row : (int64_t)sd.part_row + (int64_t)split * sd.chunk_len;
   __syncthreads();  // all rings are drained and read
-  float* sm_o = reinterpret_cast<float*>(lds);   // [wave][32][D]
-  float* sm_ml = sm_o + kWaves * 32 * D;         // [wave][32][2]
-  static_assert(kWaves * 32 * (D + 2) * 4 <= G::kLdsBytes, "combine buffer fits");
+  // (the buffer holds kCombineRows rows of every wavefront: 32 with the large ring, 16 with
+  // the small one, whose launches then take two passes if they have more rows)
+  constexpr int kCombineRows = STAGES == 2 ? 32 : 16;
+  float* sm_o = reinterpret_cast<float*>(lds);           // [wave][kCombineRows][D]
+  float* sm_ml = sm_o + kWaves * kCombineRows * D;       // [wave][kCombineRows][2]
+  static_assert(kWaves * kCombineRows * (D + 2) * 4 <= G::kLdsBytes, "combine buffer fits");
   const float lt = rb.row_sum();
-  if (valid) {
-    float* op = sm_o + (wave * 32 + col) * D + 4 * half;
+  for (int row0 = 0; row0 < n_rows; row0 += kCombineRows) {
+    const int in_pass = col - row0;
+    if (valid && in_pass >= 0 && in_pass < kCombineRows) {
+      float* op = sm_o + (wave * kCombineRows + in_pass) * D + 4 * half;
 #pragma unroll
-    for (int db = 0; db < RowBlock<D>::kDBlocks; ++db)
+      for (int db = 0; db < RowBlock<D>::kDBlocks; ++db)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        f32x4 v;
+        for (int i = 0; i < 4; ++i) {
+          f32x4 v;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = rb.o[db][4 * i + j];
-        *reinterpret_cast<f32x4*>(op + db * 32 + 8 * i) = v;
+          for (int j = 0; j < 4; ++j) v[j] = rb.o[db][4 * i + j];
+          *reinterpret_cast<f32x4*>(op + db * 32 + 8 * i) = v;
+        }
+      if (half == 0) {
+        sm_ml[(wave * kCombineRows + in_pass) * 2 + 0] = rb.m;
+        sm_ml[(wave * kCombineRows + in_pass) * 2 + 1] = lt;
       }
-    if (half == 0) {
-      sm_ml[(wave * 32 + col) * 2 + 0] = rb.m;
-      sm_ml[(wave * 32 + col) * 2 + 1] = lt;
     }
-  }
-  __syncthreads();
-  for (int e = threadIdx.x; e < n_rows * (D / 4); e += kThreads) {
-    const int r = e / (D / 4);
-    const int d4 = e % (D / 4);
-    float mw[kWaves], lw[kWaves], mm = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      mw[w] = sm_ml[(w * 32 + r) * 2 + 0];
-      lw[w] = sm_ml[(w * 32 + r) * 2 + 1];
-      mm = fmaxf(mm, mw[w]);
-    }
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    float lt_all = 0.f;
-    if (mm != -INFINITY) {
+    __syncthreads();
+    const int rows_here = min(kCombineRows, n_rows - row0);
+    for (int e = threadIdx.x; e < rows_here * (D / 4); e += kThreads) {
+      const int rl = e / (D / 4);
+      const int r = row0 + rl;
+      const int d4 = e % (D / 4);
+      float mw[kWaves], lw[kWaves], mm = -INFINITY;
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) {
-        const float a = fast_exp2(mw[w] - mm);
-        lt_all += a * lw[w];
-        const f32x4 ov = *reinterpret_cast<const f32x4*>(sm_o + (w * 32 + r) * D + d4 * 4);
-        if (lw[w] > 0.f) acc += ov * a;
+        mw[w] = sm_ml[(w * kCombineRows + rl) * 2 + 0];
+        lw[w] = sm_ml[(w * kCombineRows + rl) * 2 + 1];
+        mm = fmaxf(mm, mw[w]);
       }
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      float lt_all = 0.f;
+      if (mm != -INFINITY) {
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+          const float a = fast_exp2(mw[w] - mm);
+          lt_all += a * lw[w];
+          const f32x4 ov =
+              *reinterpret_cast<const f32x4*>(sm_o + (w * kCombineRows + rl) * D + d4 * 4);
+          if (lw[w] > 0.f) acc += ov * a;
+        }
+      }
+      const float inv = lt_all > 0.f ? 1.f / lt_all : 0.f;
+      const int64_t orow = (row_base + r / gqa) * args.h_q + kv_head * gqa + r % gqa;
+      *reinterpret_cast<f32x4*>(o_base + orow * D + d4 * 4) = acc * inv;
+      if (d4 == 0) l_base[orow] = lt_all > 0.f ? (mm + fast_log2(lt_all)) * kLn2 : -INFINITY;
     }
-    const float inv = lt_all > 0.f ? 1.f / lt_all : 0.f;
-    const int64_t orow = (row_base + r / gqa) * args.h_q + kv_head * gqa + r % gqa;
-    *reinterpret_cast<f32x4*>(o_base + orow * D + d4 * 4) = acc * inv;
-    if (d4 == 0) l_base[orow] = lt_all > 0.f ? (mm + fast_log2(lt_all)) * kLn2 : -INFINITY;
+    if (row0 + kCombineRows < n_rows) __syncthreads();  // before the next pass refills
   }
 }
 

@@ -69,9 +69,9 @@ int check_heads(int h_q, int h_kv, int d, int page_size) {
   return MEDHA_OK;
 }
 
-template <int D>
+template <int D, int STAGES>
 hipError_t launch_decode(const AttnArgs& a, int grid, hipStream_t stream) {
-  hipLaunchKernelGGL((decode_kernel<D>), dim3(grid), dim3(kThreads), 0, stream, a);
+  hipLaunchKernelGGL((decode_kernel<D, STAGES>), dim3(grid), dim3(kThreads), 0, stream, a);
   return hipGetLastError();
 }
 
@@ -107,7 +107,16 @@ hipError_t launch_plan(const LaunchPlan& lp, bool split_keys, int d, AttnArgs& a
     if (grid <= 0) continue;
     hipError_t e;
     if (split_keys) {
-      e = d == 128 ? launch_decode<128>(a, grid, stream) : launch_decode<64>(a, grid, stream);
+      // short walks: the small ring, two workgroups per compute unit (see decode_kernel)
+      int64_t steps = 0;
+      for (int i = 0; i < n; ++i)
+        steps = std::max<int64_t>(steps, std::min<int64_t>(
+            a.inline_descs[i].tiles_per_split,
+            ceil_div(a.inline_descs[i].kv_len, lp.shape.tile_keys)));
+      if (steps <= kShortWalkTiles)
+        e = d == 128 ? launch_decode<128, 1>(a, grid, stream) : launch_decode<64, 1>(a, grid, stream);
+      else
+        e = d == 128 ? launch_decode<128, 2>(a, grid, stream) : launch_decode<64, 2>(a, grid, stream);
     } else if (lp.q_blocks == 2) {
       e = d == 128 ? launch_prefill<128, 8>(a, grid, stream)
                    : launch_prefill<64, 8>(a, grid, stream);

@@ -57,7 +57,6 @@ inline void plan_launch(LaunchPlan& lp, int h_kv, int gqa, int target_wgs, int m
     total_steps += (int64_t)h_kv * sd.n_row_tiles * kv_tiles;
   }
   const int64_t steps_target = std::max<int64_t>(1, ceil_div(total_steps, target_wgs));
-  int slot = 0, rank = 0;
   for (SeqDesc& sd : lp.descs) {
     const int64_t kv_tiles = std::max<int64_t>(1, ceil_div((int64_t)sd.kv_len, sh.tile_keys));
     int64_t n_split = 1;
@@ -70,15 +69,38 @@ inline void plan_launch(LaunchPlan& lp, int h_kv, int gqa, int target_wgs, int m
     n_split = ceil_div(kv_tiles, tps);
     sd.n_split = (int)n_split;
     sd.tiles_per_split = (int)tps;
+  }
+  // Longest workgroups first: the hardware hands workgroups out in slot order, so the short
+  // ones fill the launch's tail instead of a long one starting last (the order of the
+  // sequences inside a launch is free: every descriptor carries its own rows).
+  {
+    std::vector<int> order(lp.descs.size());
+    for (size_t i = 0; i < order.size(); ++i) order[i] = (int)i;
+    auto walk = [&](int i) {
+      const SeqDesc& sd = lp.descs[i];
+      return std::min<int64_t>(sd.tiles_per_split, ceil_div((int64_t)sd.kv_len, sh.tile_keys));
+    };
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return walk(a) > walk(b); });
+    std::vector<SeqDesc> descs(order.size());
+    std::vector<int32_t> index(order.size());
+    for (size_t i = 0; i < order.size(); ++i) {
+      descs[i] = lp.descs[order[i]];
+      index[i] = lp.seq_index[order[i]];
+    }
+    lp.descs.swap(descs);
+    lp.seq_index.swap(index);
+  }
+  int slot = 0, rank = 0;
+  for (SeqDesc& sd : lp.descs) {
     sd.work_start = slot;
     sd.row_rank = rank;
     sd.part_row = 0;
-    if (n_split > 1) {
+    if (sd.n_split > 1) {
       sd.part_row = (int32_t)part_rows;
-      part_rows += n_split * sd.chunk_len;
+      part_rows += (int64_t)sd.n_split * sd.chunk_len;
       lp.any_split = true;
     }
-    const int64_t items = (int64_t)h_kv * n_split * sd.n_row_tiles;
+    const int64_t items = (int64_t)h_kv * sd.n_split * sd.n_row_tiles;
     slot += (int)(kXcds * ceil_div(items, kXcds));
     rank += sd.chunk_len;
   }
@@ -114,7 +136,7 @@ inline Plan make_plan(const SeqInput* seqs, int batch, int h_q, int h_kv, int he
   if (!plan.rows.descs.empty())
     plan_launch(plan.rows, h_kv, gqa, num_cus, 4, plan.part_rows);
   if (!plan.keys.descs.empty())
-    plan_launch(plan.keys, h_kv, gqa, num_cus * 4, 4, plan.part_rows);
+    plan_launch(plan.keys, h_kv, gqa, num_cus * 8, 4, plan.part_rows);
 
   size_t off = 0;
   plan.off_part_o = off;

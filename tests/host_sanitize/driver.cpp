@@ -7,7 +7,9 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <algorithm>
 #include <random>
+#include <utility>
 #include <vector>
 
 #include "medha.h"
@@ -51,7 +53,8 @@ static void check_plan(const std::vector<int32_t>& prefix, const std::vector<int
   CHECK(medha_describe_plan(prefix.data(), chunk.data(), n, h_q, h_kv, d, cus, e.data(),
                             &grid_rows, &grid_keys, &ws) == MEDHA_OK);
   const int gqa = h_q / h_kv;
-  int64_t end[2] = {0, 0}, part_rows = 0;
+  int64_t total[2] = {0, 0}, part_rows = 0;
+  std::vector<std::pair<int32_t, int32_t>> spans[2];  // (work_start, n_slots) per launch
   for (int i = 0; i < n; ++i) {
     const int64_t rows = (int64_t)chunk[i] * gqa;
     CHECK(e[i].mode == (rows <= 32 ? 1 : 0));
@@ -63,8 +66,8 @@ static void check_plan(const std::vector<int32_t>& prefix, const std::vector<int
     CHECK((int64_t)(e[i].n_split - 1) * e[i].tiles_per_split < kv_tiles);
     const int64_t items = (int64_t)h_kv * e[i].n_split * e[i].n_row_tiles;
     CHECK(e[i].n_slots == 8 * ceil_div(items, 8));
-    CHECK(e[i].work_start == end[e[i].mode]);
-    end[e[i].mode] += e[i].n_slots;
+    spans[e[i].mode].push_back({e[i].work_start, e[i].n_slots});
+    total[e[i].mode] += e[i].n_slots;
     if (e[i].n_split > 1) part_rows += (int64_t)e[i].n_split * chunk[i];
     if (walk_slots) {
       std::vector<char> seen((size_t)items, 0);
@@ -81,7 +84,17 @@ static void check_plan(const std::vector<int32_t>& prefix, const std::vector<int
       for (char c : seen) CHECK(c);
     }
   }
-  CHECK(grid_rows == end[0] && grid_keys == end[1]);
+  // the sequences of a launch tile its grid (in the planner's own order)
+  for (int mode = 0; mode < 2; ++mode) {
+    std::sort(spans[mode].begin(), spans[mode].end());
+    int64_t end = 0;
+    for (const auto& sp : spans[mode]) {
+      CHECK(sp.first == end);
+      end += sp.second;
+    }
+    CHECK(end == total[mode]);
+  }
+  CHECK(grid_rows == total[0] && grid_keys == total[1]);
   CHECK(ws >= (size_t)part_rows * h_q * (d + 1) * 4);
   CHECK(ws == medha_chunked_prefill_workspace_bytes(prefix.data(), chunk.data(), n, h_q, h_kv, d) ||
         cus != 0);

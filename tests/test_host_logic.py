@@ -47,7 +47,7 @@ def test_workspace_queries_reject_bad_arguments():
 def _check_plan(prefix, chunk, h_q, h_kv, d, num_cus):
     entries, grid_rows, grid_keys, ws = medha.describe_plan(prefix, chunk, h_q, h_kv, d, num_cus)
     gqa = h_q // h_kv
-    ends = {0: 0, 1: 0}
+    spans = {0: [], 1: []}
     part_rows = 0
     for p, c, e in zip(prefix, chunk, entries):
         n_rows = c * gqa
@@ -61,8 +61,7 @@ def _check_plan(prefix, chunk, h_q, h_kv, d, num_cus):
         assert (e.n_split - 1) * e.tiles_per_split < kv_tiles
         items = h_kv * e.n_split * e.n_row_tiles
         assert e.n_slots == 8 * -(-items // 8)
-        assert e.work_start == ends[e.mode]
-        ends[e.mode] += e.n_slots
+        spans[e.mode].append((e.work_start, e.n_slots, min(e.tiles_per_split, kv_tiles)))
         # every (kv head, split, row tile) is owned by exactly one slot
         seen = set()
         for s in range(e.n_slots):
@@ -83,7 +82,16 @@ def _check_plan(prefix, chunk, h_q, h_kv, d, num_cus):
             assert all(len(v) == 1 for v in dies.values())
         if e.n_split > 1:
             part_rows += e.n_split * c
-    assert grid_rows == ends[0] and grid_keys == ends[1]
+    # per launch the sequences' slot ranges tile [0, grid) in some order, and that order puts
+    # the workgroups with the longest walks first
+    for mode, grid in ((0, grid_rows), (1, grid_keys)):
+        end, prev_walk = 0, None
+        for start, n_slots, walk in sorted(spans[mode]):
+            assert start == end
+            end += n_slots
+            assert prev_walk is None or walk <= prev_walk
+            prev_walk = walk
+        assert end == grid
     need = part_rows * h_q * (d + 1) * 4
     assert need <= ws <= need + 1024 + 64 * len(prefix)
     return entries, grid_rows, grid_keys
@@ -98,9 +106,9 @@ def test_plans_of_the_named_workloads():
                             (8192, 256, 1)]:
         e, gr, _ = _check_plan([1 << 20], [c], 8, 1, 128, 256)
         assert (e[0].n_row_tiles, e[0].n_split) == (tiles, split) and gr == 256
-    # cfg3: 4 shards x 8 kv heads, split so that every compute unit streams
+    # cfg3: 4 shards x 8 kv heads, split into 8 workgroups per compute unit
     e, _, gk = _check_plan([262143] * 4, [1] * 4, 32, 8, 128, 256)
-    assert all(x.mode == 1 and x.n_split == 32 for x in e) and gk == 1024
+    assert all(x.mode == 1 and x.n_split == 64 for x in e) and gk == 2048
     # cfg1
     e, gr, _ = _check_plan([1024], [256], 2, 1, 64, 256)
     assert e[0].n_row_tiles == 2 and e[0].n_split > 1
