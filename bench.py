@@ -262,35 +262,38 @@ def main():
         del src, rsink, sink, ops
         torch.cuda.empty_cache()
     # ------------------------------------------------------------- headline
-    b = wl.config2_llama8b("cuda:0")
-    run, out, lse = prefill_runner(b)
-    t = time_calls(run, args.steps, args.warmup)
-    flops = b.algorithmic_flops()
-    ms = t["wall_ms_per_step"]
-    tflops = flops / (ms * 1e-3) / 1e12
-    kern_tflops = flops / (t["event_ms_mean"] * 1e-3) / 1e12
-    log(f"main: {ms:.4f} ms/step wall, {t['event_ms_mean']:.4f} ms events (median "
-        f"{t['event_ms_median']:.4f}, {t['settle_steps']} settling launches) -> {tflops:.1f} TFLOP/s")
-    result.update({
-        "metric": "chunked-prefill attn TFLOP/s + decode KV-read GB/s, % of MI355X roofline",
-        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "cfg2 Llama-3-8B layer chunked prefill: 32 q / 8 kv heads, d 128, "
-                               "prefix 32768 + chunk 2048, page 16, shuffled 2176-page table",
-                   "algorithmic_flops": flops, "kv_bytes": b.algorithmic_kv_bytes()},
-        "roofline": roofline("mfma", kern_tflops, "prefill_kernel<128,8,4>", t,
-                             "prefill_kernel_cfg2_pmc.txt"),
-        "settle_steps": t["settle_steps"], "ms_per_step_median": t["event_ms_median"],
-    })
-    if ceilings is not None:
-        result["ceilings"] = ceilings
-        result["roofline"]["frac_of_measured_ceiling"] = kern_tflops / ceilings["mfma_bf16_tflops"]
-    if "cpu" in sections:
-        result["cpu_baseline"] = cpu_baseline(b)
-        log(f"cpu oracle: {result['cpu_baseline']}")
-    del b, run, out, lse
-    torch.cuda.empty_cache()
+    # (left out only by profiling runs that want one workload's kernels alone: the JSON line
+    # then lacks the headline fields)
+    if "main" in sections or "cpu" in sections:
+        b = wl.config2_llama8b("cuda:0")
+        run, out, lse = prefill_runner(b)
+        t = time_calls(run, args.steps, args.warmup)
+        flops = b.algorithmic_flops()
+        ms = t["wall_ms_per_step"]
+        tflops = flops / (ms * 1e-3) / 1e12
+        kern_tflops = flops / (t["event_ms_mean"] * 1e-3) / 1e12
+        log(f"main: {ms:.4f} ms/step wall, {t['event_ms_mean']:.4f} ms events (median "
+            f"{t['event_ms_median']:.4f}, {t['settle_steps']} settling launches) -> {tflops:.1f} TFLOP/s")
+        result.update({
+            "metric": "chunked-prefill attn TFLOP/s + decode KV-read GB/s, % of MI355X roofline",
+            "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "cfg2 Llama-3-8B layer chunked prefill: 32 q / 8 kv heads, d 128, "
+                                   "prefix 32768 + chunk 2048, page 16, shuffled 2176-page table",
+                       "algorithmic_flops": flops, "kv_bytes": b.algorithmic_kv_bytes()},
+            "roofline": roofline("mfma", kern_tflops, "prefill_kernel<128,8,4>", t,
+                                 "prefill_kernel_cfg2.txt"),
+            "settle_steps": t["settle_steps"], "ms_per_step_median": t["event_ms_median"],
+        })
+        if ceilings is not None:
+            result["ceilings"] = ceilings
+            result["roofline"]["frac_of_measured_ceiling"] = kern_tflops / ceilings["mfma_bf16_tflops"]
+        if "cpu" in sections:
+            result["cpu_baseline"] = cpu_baseline(b)
+            log(f"cpu oracle: {result['cpu_baseline']}")
+        del b, run, out, lse
+        torch.cuda.empty_cache()
 
     # --------------------------------------------------------------- append
     if "append" in sections:
@@ -340,8 +343,8 @@ def main():
             "ms_median": t["event_ms_median"], "value": gbps, "unit": "GB/s",
             "kv_bytes": c.algorithmic_kv_bytes(),
             "roofline": roofline("hbm", gbps,
-                                 "decode_kernel<128> (+ split_merge_kernel, lse_merge_kernel)", t,
-                                 "decode_kernel_cfg3_pmc.txt")}
+                                 "decode_kernel<128,2> (+ split_merge_wide_kernel, lse_merge_kernel)", t,
+                                 "decode_kernel_cfg3.txt")}
         if ceilings is not None:
             result["decode"]["roofline"]["frac_of_measured_ceiling"] = \
                 gbps / ceilings["stream_lds_gbps"]
@@ -370,7 +373,7 @@ def main():
                           "us_per_token": t["event_ms_mean"] * 1e3 / chunk,
                           "algorithmic_flops": bb.algorithmic_flops(),
                           "roofline": roofline("mfma", tf, kern, t,
-                                               f"prefill_kernel_cfg4_c{chunk}_pmc.txt")})
+                                               f"prefill_kernel_cfg4_c{chunk}.txt")})
         per_tok = {p["chunk"]: p["us_per_token"] for p in sweep}
         result["sweep"] = {"workload": "cfg4 Llama-3-70B TP8 share: 8 q / 1 kv head, d 128, "
                                        "prefix 1,048,576", "points": sweep}
@@ -510,14 +513,14 @@ def main():
             "decode_part_alone_gbps": dec_bytes / (td["event_ms_mean"] * 1e-3) / 1e9,
             "roofline": roofline("mfma", (pf + 4.0 * m.d * m.h_q * float(
                 m.meta["decode_lens"].sum())) / (t["event_ms_mean"] * 1e-3) / 1e12,
-                "whole call: prefill_kernel<128,8,4> + decode_kernel<128> + split merges", t,
-                "mixed_cfg5_pmc.txt"),
+                "whole call: prefill_kernel<128,8,4> + decode_kernel<128,1> + split merges", t,
+                "mixed_cfg5.txt"),
             "prefill_part_roofline": roofline(
                 "mfma", pf / (tp["event_ms_mean"] * 1e-3) / 1e12,
                 "prefill_kernel<128,8,4> x 2 KV ranges + split merge", tp),
             "decode_part_roofline": roofline(
                 "hbm", dec_bytes / (td["event_ms_mean"] * 1e-3) / 1e9,
-                "decode_kernel<128> + split merge", td)}
+                "decode_kernel<128,1> + split merge", td)}
         del only_prefill, only_decode, run_p, run_d
         del m, run
         torch.cuda.empty_cache()
