@@ -1,24 +1,27 @@
 #!/usr/bin/env python3
 """Benchmark of the paged-attention hot path on one MI355X.
 
-A step is one call of the chunked-prefill entry point on the Llama-3-8B-shaped
-single-layer workload (32 q heads / 8 kv heads, d 128, prefix 32768 + chunk
-2048, 16-token pages, shuffled page table) with every input resident in HBM.
-`value` is algorithmic attention TFLOP/s (4*d*h_q flop per visible query-key
-pair, exact causal count) = flops per step / mean step time.
+A step is one call of the chunked-prefill entry point on the largest single-GPU
+workload: one GPU's tensor-parallel share of Llama-3-70B (8 q heads / 1 kv head,
+d 128), an 8192-token chunk against a 1,048,576-token paged prefix (16-token
+pages, shuffled page table), every input resident in HBM.  `value` is algorithmic
+attention TFLOP/s (4*d*h_q flop per visible query-key pair, exact causal count)
+= flops per step / mean step time.
 
 The same JSON line also carries, each measured in its own timed loop:
+  cfg2     the 32K-prefix workload (one Llama-3-8B layer: 32 q / 8 kv heads,
+           prefix 32768 + chunk 2048): TFLOP/s against the MFMA roofline;
   decode   the KV-cache-parallel decode workload (1M-token context as 4 shards
            of 262,144 through the decode-partial entry point, then the LSE
            merge): KV-read GB/s against the HBM roofline;
-  sweep    the Llama-3-70B tensor-parallel share (8 q / 1 kv head, 1M prefix)
-           at chunk sizes 32..8192: TFLOP/s and microseconds per token per chunk size; and, for chunk 2048,
+  sweep    the headline shape at chunk sizes 32..8192: TFLOP/s and microseconds
+           per token per chunk size; and, for chunk 2048,
            one GPU's share under KV-cache parallelism of degree 1, 2, 4, 8 (the
            chunk against one KV shard) plus the merge of the partials;
   policy   (with sweep) the paper's chunk-size policy on this device's timings:
            runtime model fitted to the sweep, chunk sizes for a 20 ms iteration,
            prefill-time cache, microseconds per decision;
-  append   the chunk's K/V scattered into the paged pools (the step before the
+  append   a chunk's K/V scattered into the paged pools (the step before the
            attention call): microseconds and GB/s;
   mixed    one 1024-token prefill chunk at a 524,288-token prefix plus 64
            decodes in one call.
@@ -31,7 +34,8 @@ and `cpu_baseline`: the fp64 CPU oracle timed on a bounded sample of rows of
 the headline workload on this machine's host cores (a reported baseline only).
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W]
-                [--sections ceilings,main,append,decode,sweep,policy,mixed,cpu[,copy]]
+                [--sections ceilings,main,cfg2,append,decode,sweep,policy,mixed,cpu[,copy]]
+                [--chunks 32,128,...]
 """
 import argparse
 import json
@@ -200,7 +204,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--sections", default="ceilings,main,append,decode,sweep,policy,mixed,cpu")
+    ap.add_argument("--sections", default="ceilings,main,cfg2,append,decode,sweep,policy,mixed,cpu")
     ap.add_argument("--chunks", default="32,128,512,1024,2048,4096,8192",
                     help="chunk lengths of the sweep section (the policy fit needs at least "
                          "three of 512 and above)")
@@ -262,13 +266,16 @@ def main():
         del src, rsink, sink, ops
         torch.cuda.empty_cache()
     # ------------------------------------------------------------- headline
-    # (left out only by profiling runs that want one workload's kernels alone: the JSON line
-    # then lacks the headline fields)
+    # the largest single-GPU configuration: one GPU's tensor-parallel share of Llama-3-70B, an
+    # 8192-token chunk against a 1,048,576-token paged prefix.  (Left out only by profiling runs
+    # that want another workload's kernels alone: the JSON line then lacks the headline fields.)
+    base = None
+    if sections & {"main", "cpu", "sweep"}:
+        base = wl.config4_llama70b_tp(8192, "cuda:0")
     if "main" in sections or "cpu" in sections:
-        b = wl.config2_llama8b("cuda:0")
-        run, out, lse = prefill_runner(b)
+        run, out, lse = prefill_runner(base)
         t = time_calls(run, args.steps, args.warmup)
-        flops = b.algorithmic_flops()
+        flops = base.algorithmic_flops()
         ms = t["wall_ms_per_step"]
         tflops = flops / (ms * 1e-3) / 1e12
         kern_tflops = flops / (t["event_ms_mean"] * 1e-3) / 1e12
@@ -279,19 +286,42 @@ def main():
             "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
             "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-            "config": {"workload": "cfg2 Llama-3-8B layer chunked prefill: 32 q / 8 kv heads, d 128, "
-                                   "prefix 32768 + chunk 2048, page 16, shuffled 2176-page table",
-                       "algorithmic_flops": flops, "kv_bytes": b.algorithmic_kv_bytes()},
+            "config": {"workload": "cfg4 Llama-3-70B tensor-parallel share, chunked prefill: 8 q / 1 kv "
+                                   "head, d 128, prefix 1,048,576 + chunk 8192, page 16, shuffled "
+                                   "66,048-page table",
+                       "algorithmic_flops": flops, "kv_bytes": base.algorithmic_kv_bytes()},
             "roofline": roofline("mfma", kern_tflops, "prefill_kernel<128,8,4>", t,
-                                 "prefill_kernel_cfg2.txt"),
+                                 "prefill_kernel_cfg4_c8192.txt"),
             "settle_steps": t["settle_steps"], "ms_per_step_median": t["event_ms_median"],
         })
         if ceilings is not None:
             result["ceilings"] = ceilings
             result["roofline"]["frac_of_measured_ceiling"] = kern_tflops / ceilings["mfma_bf16_tflops"]
         if "cpu" in sections:
-            result["cpu_baseline"] = cpu_baseline(b)
+            result["cpu_baseline"] = cpu_baseline(base)
             log(f"cpu oracle: {result['cpu_baseline']}")
+        del run, out, lse
+        torch.cuda.empty_cache()
+
+    # ----------------------------------------------------------------- cfg2
+    if "cfg2" in sections:
+        # the 32K-prefix workload: one Llama-3-8B layer, 256 workgroups of 513..544 tiles
+        b = wl.config2_llama8b("cuda:0")
+        run, out, lse = prefill_runner(b)
+        t = time_calls(run, args.steps, args.warmup)
+        tf = b.algorithmic_flops() / (t["event_ms_mean"] * 1e-3) / 1e12
+        log(f"cfg2: {t['wall_ms_per_step']:.4f} ms/step wall, {t['event_ms_mean']:.4f} ms events "
+            f"(median {t['event_ms_median']:.4f}, {t['settle_steps']} settling launches) -> "
+            f"{tf:.1f} TFLOP/s")
+        result["cfg2"] = {
+            "workload": "cfg2 Llama-3-8B layer chunked prefill: 32 q / 8 kv heads, d 128, "
+                        "prefix 32768 + chunk 2048, page 16, shuffled 2176-page table",
+            "ms": t["event_ms_mean"], "ms_wall": t["wall_ms_per_step"], "tflops": tf,
+            "algorithmic_flops": b.algorithmic_flops(), "kv_bytes": b.algorithmic_kv_bytes(),
+            "roofline": roofline("mfma", tf, "prefill_kernel<128,8,4>", t,
+                                 "prefill_kernel_cfg2.txt")}
+        if ceilings is not None:
+            result["cfg2"]["roofline"]["frac_of_measured_ceiling"] = tf / ceilings["mfma_bf16_tflops"]
         del b, run, out, lse
         torch.cuda.empty_cache()
 
@@ -354,7 +384,6 @@ def main():
     # ---------------------------------------------------------------- sweep
     if "sweep" in sections:
         sweep = []
-        base = wl.config4_llama70b_tp(8192, "cuda:0")
         chunks = [int(c) for c in args.chunks.split(",")]
         for chunk in chunks:
             bb = wl.PrefillBatch(f"cfg4_c{chunk}", base.h_q, base.h_kv, base.d, base.prefix_len,
@@ -472,8 +501,9 @@ def main():
             "workload": "cfg4 shape, chunk 2048 at prefix 1,048,576: the chunk against the last of "
                         "S page-aligned KV shards (one GPU's share under KVP degree S) and the "
                         "LSE merge of S partials", "points": kvp}
-        del base, pt_dev, qc
-        torch.cuda.empty_cache()
+        del pt_dev, qc
+    del base
+    torch.cuda.empty_cache()
 
     # ---------------------------------------------------------------- mixed
     if "mixed" in sections:
