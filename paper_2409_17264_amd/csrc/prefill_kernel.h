@@ -381,10 +381,11 @@ struct RowBlock {
   // check is one comparison of two registers.  A failed check takes the exact route for
   // those two slices -- maximum, move of the reference point, rescale, new
   // probabilities -- and evens out the sums of the two lanes that share a row (a lane
-  // whose keys so far happen to weigh little would otherwise keep failing).  The first
-  // few hundred keys of a walk always take that route (the sum is still small), and so
-  // do keys that bring a sizeable share of their row; everything else -- nearly all of
-  // a long walk -- passes.  Diagonal tiles (MASK true) always take the exact route.
+  // whose keys so far happen to weigh little would otherwise keep failing).  Keys that
+  // bring a sizeable share of their row take that route; everything else -- nearly all
+  // of a long walk -- passes.  While the sum is still small (the head of a walk) every
+  // check would fail: those tiles do not speculate at all (SPEC false, see run_tiles()).
+  // Diagonal tiles (MASK true) always take the exact route.
   static constexpr float kSpecShare = 1.f / 16.f;
 
   __device__ __forceinline__ void add_to_sum(float ls) { l = __builtin_fmaf(ls, kSpecShare, l); }
@@ -415,11 +416,13 @@ struct RowBlock {
 
   //
   // QK false leaves the next tile out (the walk's last tile): the same slots without
-  // their K reads and S^T MFMAs; k_next and sn are not touched.
-  template <bool MASK, bool QK = true>
+  // their K reads and S^T MFMAs; k_next and sn are not touched.  SPEC false takes the
+  // exact route (row maximum first) also on an unmasked tile: for the first tiles of a
+  // walk, whose speculation would fail anyway, it is the cheaper of the two.
+  template <bool MASK, bool QK = true, bool SPEC = true>
   __device__ __forceinline__ void fused(const char* k_next, const char* v_cur, f32x16 (&sc)[2],
                                         f32x16 (&sn)[2], int key0, int half) {
-    constexpr bool kSpec = !MASK;
+    constexpr bool kSpec = SPEC && !MASK;
     constexpr int kQk = 2 * kSlices;       // MFMAs of the next tile's S^T
     constexpr int kPv = 4 * kDBlocks;      // MFMAs of the current tile's O^T
     constexpr int kSlots = kQk + kPv;
@@ -568,6 +571,12 @@ struct PrefillShape {
   static constexpr int kLdsBytes = NS * kStageBytes;
 };
 
+// Tiles at the head of an unmasked walk that take the exact route without speculating
+// first (a multiple of the ring's stage count).  Measured on walks of 65 to 4100 tiles:
+// 24 to 32 is best; 8 and 12 leave failed checks behind, with every tile exact the long
+// walks take 4 % longer.
+constexpr int kWarmTiles = 24;
+
 // The ring: NS stages of (K tile, V tile), contiguous from `base`.
 struct Ring {
   char* base;         // for operand reads
@@ -612,7 +621,9 @@ __device__ __forceinline__ void run_tiles(RowBlock<D>& rb, const AttnArgs& args,
     for (int f = 0; f < 32; ++f) mx = fmaxf(mx, s0[f >> 4][f & 15]);
     rb.template update_reference<false>(mx);
   }
-  for (int kt = kt_a; kt < last; kt += NS) {
+  // One group of NS iterations starting at tile kt (stage numbers are compile-time).
+  auto group = [&](int kt, auto spec) {
+    constexpr bool kSpeculate = decltype(spec)::value;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       const int cur = kt + s;
@@ -626,9 +637,11 @@ __device__ __forceinline__ void run_tiles(RowBlock<D>& rb, const AttnArgs& args,
         const char* k_next = ring.base + ((s + 1) % NS) * kTile;
         const char* v_cur = ring.base + s * kTile;  // + the bias in rb.v_off
         if (s & 1)
-          rb.template fused<MASK>(k_next, v_cur, s1, s0, cur * G::kTileKeys, half);
+          rb.template fused<MASK, true, kSpeculate>(k_next, v_cur, s1, s0, cur * G::kTileKeys,
+                                                    half);
         else
-          rb.template fused<MASK>(k_next, v_cur, s0, s1, cur * G::kTileKeys, half);
+          rb.template fused<MASK, true, kSpeculate>(k_next, v_cur, s0, s1, cur * G::kTileKeys,
+                                                    half);
         // The scalar load of the next page id goes HERE, after the tile's last LDS read has
         // been consumed and before the barrier: scalar loads and LDS reads share one
         // counter and scalar loads return out of order, so with one in flight every wait for
@@ -639,7 +652,17 @@ __device__ __forceinline__ void run_tiles(RowBlock<D>& rb, const AttnArgs& args,
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+  };
+  int kt = kt_a;
+  if constexpr (!MASK) {
+    // The speculation check of fused() cannot pass before a lane's sum is 16 times what two
+    // slices bring: not in the first 8 tiles of a walk of diffuse rows, and with 64 lanes
+    // voting and the odd large score, rarely in the first twenty.  A failed check costs a
+    // multiple of what the row maximum costs when it is taken up front, so the head of the
+    // walk takes it up front.
+    for (; kt < last && kt < kt_a + kWarmTiles; kt += NS) group(kt, std::false_type{});
   }
+  for (; kt < last; kt += NS) group(kt, std::true_type{});
   // the last tile: its scores are in registers, its V tile landed with its K tile
   {
     const char* v_last = ring.base + ((last - kt_a) % NS) * kTile;  // + the bias in rb.v_off
