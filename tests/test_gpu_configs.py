@@ -85,10 +85,10 @@ def test_config5_full_size_sampled_rows():
 
 
 def test_config4_full_size_chunk_kvp_and_small_chunk():
-    """The two other launch shapes bench.py times on the 1M-token cache: a 2048-token chunk
-    against 4 page-aligned KV shards (only the last causal) merged with the LSE merge, and a
-    32-token chunk whose KV axis is split 253 ways; both against oracle rows sampled one by one
-    from plain chunked prefill."""
+    """The other launch shapes bench.py times on the 1M-token cache: a 2048-token chunk
+    against 4 page-aligned KV shards (only the last causal) merged with the LSE merge, a
+    32-token chunk whose KV axis is split 253 ways and a 128-token chunk (4 row tiles x 64 KV
+    ranges); all against oracle rows sampled one by one from plain chunked prefill."""
     b = wl.config4_llama70b_tp(2048, "cuda:0")
     prefix, chunk, shards = int(b.prefix_len[0]), 2048, 4
     n = prefix + chunk
@@ -103,10 +103,10 @@ def test_config4_full_size_chunk_kvp_and_small_chunk():
         b.scale)
     o, l = medha.lse_merge(po.view(shards, chunk, b.h_q, b.d), pl.view(shards, chunk, b.h_q))
     torch.cuda.synchronize()
-    rows = np.array([0, 1000, chunk - 1], np.int64)
+    rows = edge_rows(b, 77, 4, 4, 6, 2)
     ro, rl = oracle_prefill(b, rows)
     check(o.cpu().numpy()[rows], l.cpu().numpy()[rows], ro, rl,
-          "cfg4 c2048 as 4 KV shards + merge, 3 sampled rows x 8 heads")
+          f"cfg4 c2048 as 4 KV shards + merge, {len(rows)} sampled rows x 8 heads")
     # the same cache, first 32 tokens of the chunk only
     small = wl.PrefillBatch("cfg4_c32", b.h_q, b.h_kv, b.d, b.prefix_len, np.array([32], np.int32),
                             b.page_table, b.page_table_offs, b.num_pages, b.q[:32].contiguous(),
@@ -115,6 +115,17 @@ def test_config4_full_size_chunk_kvp_and_small_chunk():
                                      small.d)
     assert e[0].n_split > 200
     out, lse = gpu_prefill(small)
-    rows = np.array([0, 31], np.int64)
+    rows = np.arange(32, dtype=np.int64)
     ro, rl = oracle_prefill(small, rows)
-    check(out[rows], lse[rows], ro, rl, "cfg4 c32 (253-way split), 2 sampled rows x 8 heads")
+    check(out[rows], lse[rows], ro, rl, "cfg4 c32 (253-way split), all 32 rows x 8 heads")
+    # and the first 128 tokens: 4 row tiles x 64 KV ranges
+    mid = wl.PrefillBatch("cfg4_c128", b.h_q, b.h_kv, b.d, b.prefix_len, np.array([128], np.int32),
+                          b.page_table, b.page_table_offs, b.num_pages, b.q[:128].contiguous(),
+                          b.k_pool, b.v_pool, b.scale)
+    e, _, _, _ = medha.describe_plan(mid.prefix_len, mid.chunk_len, mid.h_q, mid.h_kv, mid.d)
+    assert e[0].n_row_tiles == 4 and e[0].n_split == 64
+    out, lse = gpu_prefill(mid)
+    rows = edge_rows(mid, 78, 4, 4, 8, 4)
+    ro, rl = oracle_prefill(mid, rows)
+    check(out[rows], lse[rows], ro, rl,
+          f"cfg4 c128 (4 row tiles x 64 KV ranges), {len(rows)} sampled rows x 8 heads")
