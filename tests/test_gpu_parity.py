@@ -7,7 +7,8 @@ import torch
 import oracle
 import paper_2409_17264_amd as medha
 from paper_2409_17264_amd import workloads as wl
-from tests.gpu_util import (LSE_TOL, O_TOL, check, gpu_prefill, oracle_prefill, to_dev)
+from tests.gpu_util import (LSE_TOL, O_TOL, check, edge_rows, gpu_prefill, oracle_prefill,
+                            to_dev)
 
 pytestmark = pytest.mark.gpu
 
@@ -511,6 +512,20 @@ def test_small_chunk_long_prefix_many_way_split(h_q, h_kv, d, prefix, chunk):
 
 
 # ------------------------------------------------------------ softmax scale values
+@pytest.mark.parametrize("d,prefix", [(128, 64 * 20 + 7), (128, 64 * 23), (64, 64 * 22 - 1)])
+def test_walks_that_end_around_the_exact_route_warm_up(d, prefix):
+    """A launch that fills the device without a KV split (8 kv heads x 32 row tiles), whose
+    walks are 21 to 56 tiles long: they leave the exact-route head of the walk (24 tiles) after
+    0 to 32 speculative tiles, at every position of the 4-stage ring."""
+    b = to_dev(wl.make_prefill_batch("warm", 32, 8, d, [prefix], [2048], seed=prefix + d))
+    e, grid_rows, _, _ = medha.describe_plan(b.prefix_len, b.chunk_len, b.h_q, b.h_kv, b.d)
+    assert e[0].n_split == 1 and grid_rows == 256
+    out, lse = gpu_prefill(b)
+    rows = edge_rows(b, prefix, 8, 8, 40, 24)
+    ro, rl = oracle_prefill(b, rows)
+    check(out[rows], lse[rows], ro, rl, f"d{d} P{prefix} c2048, {len(rows)} sampled rows")
+
+
 @pytest.mark.parametrize("scale", [0.0, -0.1, 0.5, 1e-3, -2.0])
 def test_softmax_scale_values(scale):
     """The scale is an argument, not 1/sqrt(d) by construction: zero (uniform weights), negative
