@@ -564,8 +564,8 @@ def test_peaked_rows_long_prefix(d, scale):
 # ------------------------------------------------------ seeded random batch mixes
 @pytest.mark.parametrize("seed", range(12))
 def test_random_batches(seed):
-    """Seeded random batches: head counts, head dim, 1..70 sequences (more than 64 puts the
-    descriptors in the workspace), prefixes 0..3000 and chunks 1..260 in any mix, so that
+    """Seeded random batches: head counts, head dim, 1..70 sequences (more than 64 are
+    launched in groups), prefixes 0..3000 and chunks 1..260 in any mix, so that
     sequences of both kernels, split and unsplit, share one call."""
     rng = np.random.default_rng(1000 + seed)
     h_kv = int(rng.choice([1, 2, 4, 8]))
