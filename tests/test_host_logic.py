@@ -127,3 +127,20 @@ def test_plans_of_ragged_batches():
     # a decode over zero keys is planned too
     e, _, _ = _check_plan([-1, 0], [1, 1], 8, 2, 128, 256)
     assert e[0].n_split == 1
+
+
+def test_bench_refuses_more_than_one_gpu_and_finds_its_traffic_figures():
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                         capture_output=True, text=True, timeout=120)
+    assert res.returncode != 0 and "one GPU" in res.stderr
+    # every counter summary bench.py reads an HBM figure from is there and holds one
+    src = open(os.path.join(ROOT, "bench.py")).read()
+    names = set(re.findall(r'"([a-z0-9_]+\.txt)"', src))
+    names |= {f"prefill_kernel_cfg4_c{c}.txt" for c in (32, 128, 512, 1024, 2048, 4096, 8192)}
+    assert {"prefill_kernel_cfg2.txt", "decode_kernel_cfg3.txt", "mixed_cfg5.txt"} <= names
+    for name in sorted(names):
+        lines = [l for l in open(os.path.join(ROOT, "profiles", name))
+                 if l.startswith("hbm_bytes_per_launch")]
+        assert lines and float(lines[0].split("=")[1].split()[0]) > 1e6, name
