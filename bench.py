@@ -294,6 +294,13 @@ def main():
                                  "prefill_kernel_cfg4_c8192.txt"),
             "settle_steps": t["settle_steps"], "ms_per_step_median": t["event_ms_median"],
         })
+        result["roofline"]["traffic_note"] = (
+            "FETCH_SIZE + WRITE_SIZE count what the L2s fill from the fabric, Infinity Cache hits "
+            "included: the 256 row tiles of this launch stream the same 0.54 GB of K/V and each of "
+            "the 8 XCDs' L2s fills it once; over a 28 ms launch that is 0.16 TB/s of an 8 TB/s "
+            "part, on a kernel bound by the matrix pipe (algorithmic bytes: %.2e)"
+            % (base.algorithmic_kv_bytes() + 2.0 * base.tokens * base.h_q * base.d
+               + 4.0 * base.tokens * base.h_q * (base.d + 1)))
         if ceilings is not None:
             result["ceilings"] = ceilings
             result["roofline"]["frac_of_measured_ceiling"] = kern_tflops / ceilings["mfma_bf16_tflops"]
