@@ -598,6 +598,7 @@ __device__ __forceinline__ void run_tiles(RowBlock<D>& rb, const AttnArgs& args,
                                           int wave, int lane) {
   using G = TileGeom<D, NW>;
   static_assert(NS == 4, "stages: tile cur, cur+1, cur+2 (in flight), cur+3 (being issued)");
+  static_assert(kWarmTiles % NS == 0, "the walk's head is a whole number of ring rounds");
   constexpr int kTile = G::kTileBytes;  // K tiles fill the low half of the ring, V tiles the high
   if (kt_a >= kt_b) return;
   const int half = lane >> 5;
